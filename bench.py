@@ -1,0 +1,230 @@
+#!/usr/bin/env python3
+"""Benchmark of the diagonally-sparse layer's hot path on one MI355X.
+
+A step is one pass of the whole path over one batch: dd_select_diagonals, dd_fwd, dd_bwd_input
+and dd_bwd_weight of the ViT-Base attention projection (768 -> 768, 90 % sparse, K = 77,
+12608 tokens, bf16 storage, fp32 accumulation) with inputs already resident in HBM.  The
+metric is the effective (sparse) rate 3 * 2*T*K*L / t_step.  Buffers rotate over several sets
+so that a step does not find its operands in the 256 MB Infinity Cache.
+
+Prints ONE JSON line.  Besides the contract fields it carries
+  roofline      the dominant kernel against the ceiling that bounds it,
+  cpu_baseline  the CPU oracle timed on this host's cores (a baseline, not a target),
+  breakdown     per-function times, the dense bf16 GEMM (hipBLASLt through torch.matmul) of the
+                same shape, and the paper's own speedups for context.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+VALU_FP32_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published (256 CU x 128 lanes-flop x 2 x 2.4 GHz)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--sets", type=int, default=8, help="rotating buffer sets (working set > Infinity Cache)")
+    ap.add_argument("--workload", default="vitb_attn_proj")
+    ap.add_argument("--algo", default="auto", choices=["auto", "vector", "matrix"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    return ap.parse_args()
+
+
+def time_loop(torch, fn, sets, steps, warmup):
+    """Average milliseconds per call of fn(i % sets), timed with events on the launch stream."""
+    for i in range(warmup):
+        fn(i % sets)
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for i in range(steps):
+        fn(i % sets)
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) / steps
+
+
+def cpu_baseline(layer, offsets, values, X, dY, scores):
+    """The oracle, as it stands, on the host cores: the whole workload, repeated for ~10 s."""
+    from oracle import dd_oracle as orc
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        orc.select(scores, layer.K)
+        orc.fwd(X, offsets, values, layer.out_features)
+        orc.bwd_input(dY, offsets, values, layer.in_features)
+        orc.bwd_weight(X, dY, offsets)
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt > 10.0 or reps >= 5:
+            break
+    flops = 3 * 2.0 * layer.tokens * layer.K * layer.L * reps
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"whole {layer.name} workload (select + fwd + bwd_input + bwd_weight, all {layer.tokens} "
+                      f"tokens), {reps} repetitions, {dt:.1f} s; dense fp64 loops, so it performs "
+                      f"{layer.D / layer.K:.1f}x the sparse flops it is credited with"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 (no multi-GPU path exists).",
+              file=sys.stderr)
+        return 2
+    import torch
+    import paper_2506_11449_amd as dd
+    from paper_2506_11449_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    dd.load_library()
+    algo = {"auto": dd.DD_ALGO_AUTO, "vector": dd.DD_ALGO_VECTOR, "matrix": dd.DD_ALGO_MATRIX}[args.algo]
+
+    layer = synth.WORKLOADS[args.workload][0]
+    T, M, N, K, L, D = layer.tokens, layer.in_features, layer.out_features, layer.K, layer.L, layer.D
+    tdtype = torch.bfloat16 if layer.dtype == "bf16" else torch.float32
+
+    def dev(a):
+        if layer.dtype == "bf16":
+            return torch.from_numpy(synth.bf16_bits(a).view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(a).cuda()
+
+    # set 0 holds the seeded inputs; the other sets are device-side copies (same values, other addresses)
+    offsets, values, X, dY = synth.layer_inputs(layer, seed=2506)
+    scores = synth.draw_scores(1, D, seed=2506)
+    S = max(1, args.sets)
+    d_val = dev(values)
+    d_scores = torch.from_numpy(scores).cuda()
+    d_X = [dev(X)] + [None] * (S - 1)
+    d_dY = [dev(dY)] + [None] * (S - 1)
+    for s in range(1, S):
+        d_X[s], d_dY[s] = d_X[0].clone(), d_dY[0].clone()
+    d_Y = [torch.empty((T, N), dtype=tdtype, device="cuda") for _ in range(S)]
+    d_dX = [torch.empty((T, M), dtype=tdtype, device="cuda") for _ in range(S)]
+    d_dV = torch.empty((K, L), dtype=torch.float32, device="cuda")
+    d_off = torch.empty((1, K), dtype=torch.int32, device="cuda")
+    ws = dd.Workspace()
+
+    def f_select(s):
+        dd.dd_select_diagonals(d_scores, K, offsets_out=d_off, ws=ws)
+
+    def f_fwd(s):
+        dd.dd_fwd(d_X[s], d_off[0], d_val, N, Y=d_Y[s], algo=algo, ws=ws)
+
+    def f_bwd_input(s):
+        dd.dd_bwd_input(d_dY[s], d_off[0], d_val, M, dX=d_dX[s], algo=algo, ws=ws)
+
+    def f_bwd_weight(s):
+        dd.dd_bwd_weight(d_X[s], d_dY[s], d_off[0], dValues=d_dV, algo=algo, ws=ws)
+
+    def step(s):
+        f_select(s)
+        f_fwd(s)
+        f_bwd_input(s)
+        f_bwd_weight(s)
+
+    f_select(0)
+    torch.cuda.synchronize()
+
+    # ---- the timed region of the contract: W warm-up steps, then exactly K steps ----
+    for i in range(args.warmup):
+        step(i % S)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i % S)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    flops_product = 2.0 * T * K * L
+    value = 3 * flops_product / (ms_per_step * 1e-3) / 1e12
+
+    # ---- per-function device times (events on the launch stream) ----
+    n = max(20, args.steps)
+    per = {name: time_loop(torch, fn, S, n, 5) for name, fn in
+           (("dd_select_diagonals", f_select), ("dd_fwd", f_fwd), ("dd_bwd_input", f_bwd_input),
+            ("dd_bwd_weight", f_bwd_weight))}
+    hot = {name: time_loop(torch, fn, 1, n, 5) for name, fn in
+           (("dd_fwd", f_fwd), ("dd_bwd_input", f_bwd_input), ("dd_bwd_weight", f_bwd_weight))}
+
+    e = 2 if layer.dtype == "bf16" else 4
+    bytes_product = e * (T * M + T * N) + e * K * L + 4 * K
+    bytes_wgrad = e * (T * M + T * N) + 4 * K * L + 4 * K
+    dominant = max(("dd_fwd", "dd_bwd_input", "dd_bwd_weight"), key=lambda k: per[k])
+    dom_s = per[dominant] * 1e-3
+    dom_bytes = bytes_wgrad if dominant == "dd_bwd_weight" else bytes_product
+    intensity = flops_product / dom_bytes
+    # the ceiling that binds: flops / 157.3 TFLOP/s against bytes / 8 TB/s
+    alu_bound = flops_product / (VALU_FP32_PEAK_TFLOPS * 1e12) >= dom_bytes / (HBM_PEAK_GBS * 1e9)
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(args.workload, {}).get(dominant)
+        except Exception:
+            traffic = None
+    if alu_bound:
+        achieved = flops_product / dom_s / 1e12
+        roofline = {"bound": "alu", "achieved": achieved, "peak": VALU_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / VALU_FP32_PEAK_TFLOPS, "traffic": traffic}
+    else:
+        achieved = dom_bytes / dom_s / 1e9
+        roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": traffic}
+    roofline.update({"kernel": dominant, "avg_launch_us": dom_s * 1e6, "flops_per_launch": flops_product,
+                     "bytes_per_launch": dom_bytes, "flop_per_byte": intensity,
+                     "achieved_tflops": flops_product / dom_s / 1e12, "achieved_gbs": dom_bytes / dom_s / 1e9})
+
+    breakdown = {"us": {k: v * 1e3 for k, v in per.items()},
+                 "us_cache_hot": {k: v * 1e3 for k, v in hot.items()},
+                 "sparse_tflops": {k: flops_product / (per[k] * 1e-3) / 1e12
+                                   for k in ("dd_fwd", "dd_bwd_input", "dd_bwd_weight")},
+                 "dense_equivalent_tflops": {k: 2.0 * T * M * N / (per[k] * 1e-3) / 1e12
+                                             for k in ("dd_fwd", "dd_bwd_input", "dd_bwd_weight")},
+                 "paper_context": "paper reports 3.13x inference / 1.59x training speedup at 90 % sparsity, "
+                                  "ViT-Base end to end, on an A100 (abstract, Sec. 4.2.3): another machine"}
+
+    if not args.no_dense:
+        # dense bf16 GEMMs of the same shape (hipBLASLt / rocBLAS via torch.matmul), same rotation
+        Wd = torch.randn((M, N), device="cuda", dtype=tdtype) * 0.02
+        dWd = torch.empty((M, N), device="cuda", dtype=tdtype)
+        g_fwd = time_loop(torch, lambda s: torch.matmul(d_X[s], Wd, out=d_Y[s]), S, n, 5)
+        g_dgrad = time_loop(torch, lambda s: torch.matmul(d_dY[s], Wd.t(), out=d_dX[s]), S, n, 5)
+        g_wgrad = time_loop(torch, lambda s: torch.matmul(d_X[s].t(), d_dY[s], out=dWd), S, n, 5)
+        breakdown["dense_gemm_us"] = {"fwd": g_fwd * 1e3, "dgrad": g_dgrad * 1e3, "wgrad": g_wgrad * 1e3}
+        breakdown["speedup_vs_dense"] = {
+            "fwd": g_fwd / per["dd_fwd"],
+            "training": (g_fwd + g_dgrad + g_wgrad) / (per["dd_fwd"] + per["dd_bwd_input"] + per["dd_bwd_weight"])}
+
+    out = {
+        "metric": "diag-sparse linear fwd+bwd effective TFLOP/s, % roofline, speedup vs dense GEMM",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": layer.dtype, "data": "synthetic",
+        "config": {"workload": f"ViT-Base attention projection: {M}->{N}, 90% sparse (K={K} diagonals), "
+                               f"tokens={T}, bf16 storage, fp32 accumulate" if args.workload == "vitb_attn_proj"
+                   else layer.name,
+                   "step": "dd_select_diagonals + dd_fwd + dd_bwd_input + dd_bwd_weight",
+                   "algo": args.algo, "buffer_sets": S, "tokens": T, "in_features": M, "out_features": N, "K": K},
+        "roofline": roofline,
+        "breakdown": breakdown,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(layer, offsets, values, X, dY, scores)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

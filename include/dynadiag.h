@@ -1,0 +1,127 @@
+/*
+ * dynadiag.h -- C ABI of the diagonally-sparse linear layer for AMD MI355X (gfx950).
+ *
+ * The layer is the one of "Dynamic Sparse Training of Diagonally Sparse Networks"
+ * (DynaDiag, arxiv 2506.11449): a weight matrix W [in_features x out_features] that holds
+ * only K wrapped diagonals, each stored as an (offset, value-vector) pair (Sec. 3.1, Eq. 1-3).
+ *
+ * Index convention (Sec. 3.1 Eq. 1 and Appendix A; M = in_features, N = out_features):
+ *   D = max(M, N) is the number of candidate diagonals and the wrap modulus,
+ *   L = min(M, N) is the length of every diagonal.
+ *   Position p in [0, L) of diagonal k lies at long-side index q = (p + o_k) mod D, and
+ *     M <= N :  W[p, q] += values[k][p]        (Appendix A, case m < n; Eq. 1 for squares)
+ *     M >  N :  W[q, p] += values[k][p]        (Appendix A, case m >= n)
+ *   o_k = offsets[k] reduced modulo D into [0, D); any int32 is accepted, a negative offset
+ *   is a diagonal below the main one.  Repeated offsets are legal and add (Eq. 3 is a sum).
+ *   The importance weight of Eq. 4 is not an argument: the caller passes the effective
+ *   values alpha_k * V_k.
+ *
+ * Common rules for every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library never
+ *     allocates, frees or keeps device memory; scratch comes from the caller's `ws`
+ *     (size from dd_workspace_bytes, 256-byte aligned; may be NULL when that size is 0).
+ *   - All matrices are row-major and contiguous.  Inputs and outputs must not overlap.
+ *   - Outputs are overwritten.  Work is enqueued on `hip_stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and the call returns without waiting for it.
+ *   - Errors are reported by the return value; nothing is thrown and nothing aborts.
+ *     DD_ERR_INVALID_ARG: null pointer, tokens < 0, features < 1, K < 1, K > D, unknown
+ *     dtype or algo.  DD_ERR_WORKSPACE: ws_bytes below dd_workspace_bytes or ws misaligned.
+ *     DD_ERR_UNSUPPORTED: a size the kernels do not cover (stated per function).
+ *     DD_ERR_HIP: the launch itself failed.
+ *   - tokens == 0 is legal: fwd / bwd_input return DD_OK without a launch; bwd_weight
+ *     writes zeros.
+ */
+#ifndef DYNADIAG_H
+#define DYNADIAG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DD_OK = 0,
+    DD_ERR_INVALID_ARG = 1,
+    DD_ERR_UNSUPPORTED = 2,
+    DD_ERR_WORKSPACE = 3,
+    DD_ERR_HIP = 4
+} dd_status;
+
+/* Storage type of X, dY, Y, dX and values.  Accumulation is always fp32. */
+typedef enum { DD_F32 = 0, DD_BF16 = 1 } dd_dtype;
+
+/* Which kernel family runs the product.  DD_ALGO_AUTO picks by shape and density. */
+typedef enum {
+    DD_ALGO_AUTO = 0,
+    DD_ALGO_VECTOR = 1, /* direct diagonal kernels on the vector ALUs: work ~ tokens*K*L   */
+    DD_ALGO_MATRIX = 2  /* W tiles rebuilt on chip and multiplied on the matrix cores       */
+} dd_algo;
+
+typedef enum { DD_OP_FWD = 0, DD_OP_BWD_INPUT = 1, DD_OP_BWD_WEIGHT = 2, DD_OP_SELECT = 3 } dd_op;
+
+typedef struct {
+    int64_t tokens;       /* T: rows of X / dY                                   */
+    int32_t in_features;  /* M: columns of X, rows of W                          */
+    int32_t out_features; /* N: columns of Y, columns of W                       */
+    int32_t K;            /* number of active diagonals, 1 <= K <= max(M, N)     */
+    int32_t dtype;        /* dd_dtype                                            */
+    int32_t algo;         /* dd_algo                                             */
+} dd_layer;
+
+/*
+ * Bytes of device scratch that `op` needs for this layer (for DD_OP_SELECT: layer->in_features
+ * is read as D, layer->K as K, and `batch` is the number of score vectors; otherwise `batch`
+ * is ignored).  Returns 0 for arguments the op would reject.
+ */
+size_t dd_workspace_bytes(int op, const dd_layer *layer, int32_t batch);
+
+/*
+ * Forward product Y = X . W_K  (Sec. 3.1 Eq. 3; Fig. 3 b-e).
+ *   X       [tokens x M]  dtype          in
+ *   offsets [K]           int32          in   one offset per diagonal, any order
+ *   values  [K x L]       dtype          in   values[k][p] belongs to offsets[k]
+ *   Y       [tokens x N]  dtype          out  rounded to nearest-even from the fp32 sum
+ */
+dd_status dd_fwd(const dd_layer *layer, const void *X, const int32_t *offsets, const void *values,
+                 void *Y, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Backward product with respect to the input, dX = dY . W_K^T, over the same diagonals
+ * (Sec. 3.3: the transposed matrix is again diagonal-sparse with the same starts, Appendix A).
+ *   dY [tokens x N] in,  dX [tokens x M] out;  offsets / values exactly as given to dd_fwd.
+ */
+dd_status dd_bwd_input(const dd_layer *layer, const void *dY, const int32_t *offsets,
+                       const void *values, void *dX, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Backward product with respect to the values on the K diagonals (Fig. 3 h, i): the dense
+ * gradient X^T . dY restricted to the entries each diagonal owns, i.e. a sum over tokens,
+ *   dValues[k][p] = sum_t X[t, row(k,p)] * dY[t, col(k,p)].
+ *   X [tokens x M] in, dY [tokens x N] in, dValues [K x L] fp32 out (always fp32).
+ * The sum over tokens is split into fixed chunks that are added in a fixed order: two calls
+ * on the same inputs give bit-identical results.
+ */
+dd_status dd_bwd_weight(const dd_layer *layer, const void *X, const void *dY, const int32_t *offsets,
+                        float *dValues, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Hard TopK re-selection of the active diagonals (Sec. 3.2, Eq. 4): for each of `batch`
+ * score vectors alpha [D], the indices of the K largest scores.
+ *   Order between scores: larger first; equal scores (and -0 / +0) by lower index; NaN ranks
+ *   below every number.  The K chosen indices are written in ascending order, so the output
+ *   row can be handed to dd_fwd / dd_bwd_* as `offsets` without leaving the device.
+ *   scores      [batch x D] fp32   in
+ *   offsets_out [batch x K] int32  out
+ * DD_ERR_UNSUPPORTED if D > 65536.
+ */
+dd_status dd_select_diagonals(int32_t batch, int32_t D, int32_t K, const float *scores,
+                              int32_t *offsets_out, void *ws, size_t ws_bytes, void *hip_stream);
+
+const char *dd_status_string(dd_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DYNADIAG_H */

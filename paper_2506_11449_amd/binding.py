@@ -1,0 +1,184 @@
+"""Thin Python binding of libdynadiag.so: argument marshalling only.
+
+Same names as the C ABI (include/dynadiag.h).  Tensors are torch tensors on the GPU; torch is
+used for device memory and for the current stream handle, nothing else.  There is no fallback:
+if the shared library is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import torch  # imported before the library so that both share one HIP runtime
+
+from .build import LIB_PATH
+
+DD_F32, DD_BF16 = 0, 1
+DD_ALGO_AUTO, DD_ALGO_VECTOR, DD_ALGO_MATRIX = 0, 1, 2
+DD_OP_FWD, DD_OP_BWD_INPUT, DD_OP_BWD_WEIGHT, DD_OP_SELECT = 0, 1, 2, 3
+
+EXPORTS = ("dd_workspace_bytes", "dd_fwd", "dd_bwd_input", "dd_bwd_weight", "dd_select_diagonals",
+           "dd_status_string")
+
+
+class DynaDiagError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"dynadiag: {message} (status {status})")
+        self.status = status
+
+
+class dd_layer(ctypes.Structure):
+    _fields_ = [("tokens", ctypes.c_int64), ("in_features", ctypes.c_int32), ("out_features", ctypes.c_int32),
+                ("K", ctypes.c_int32), ("dtype", ctypes.c_int32), ("algo", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def load_library():
+    """dlopen libdynadiag.so and declare the prototypes.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise DynaDiagError(-1, f"{LIB_PATH} is not built; run `python -m paper_2506_11449_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32
+    lp = ctypes.POINTER(dd_layer)
+    lib.dd_workspace_bytes.argtypes = [ctypes.c_int, lp, i32]
+    lib.dd_workspace_bytes.restype = sz
+    lib.dd_fwd.argtypes = [lp, vp, vp, vp, vp, vp, sz, vp]
+    lib.dd_bwd_input.argtypes = [lp, vp, vp, vp, vp, vp, sz, vp]
+    lib.dd_bwd_weight.argtypes = [lp, vp, vp, vp, vp, vp, sz, vp]
+    lib.dd_select_diagonals.argtypes = [i32, i32, i32, vp, vp, vp, sz, vp]
+    for name in ("dd_fwd", "dd_bwd_input", "dd_bwd_weight", "dd_select_diagonals"):
+        getattr(lib, name).restype = ctypes.c_int
+    lib.dd_status_string.argtypes = [ctypes.c_int]
+    lib.dd_status_string.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(status):
+    if status != 0:
+        raise DynaDiagError(status, load_library().dd_status_string(status).decode())
+
+
+_DTYPES = {torch.float32: DD_F32, torch.bfloat16: DD_BF16}
+
+
+def make_layer(tokens, in_features, out_features, K, dtype, algo=DD_ALGO_AUTO):
+    if isinstance(dtype, torch.dtype):
+        dtype = _DTYPES[dtype]
+    return dd_layer(int(tokens), int(in_features), int(out_features), int(K), int(dtype), int(algo))
+
+
+def dd_workspace_bytes(op, layer, batch=0):
+    return int(load_library().dd_workspace_bytes(int(op), ctypes.byref(layer), int(batch)))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _dev(t, dtype, shape, name):
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous GPU tensor")
+    if t.dtype != dtype or tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: expected {dtype} {tuple(shape)}, got {t.dtype} {tuple(t.shape)}")
+    return t
+
+
+class Workspace:
+    """A reusable block of device scratch, grown on demand by the caller's side of the ABI."""
+
+    def __init__(self):
+        self.buf = None
+
+    def get(self, nbytes, device):
+        if nbytes == 0:
+            return None, 0
+        if self.buf is None or self.buf.numel() < nbytes or self.buf.device != device:
+            self.buf = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        return self.buf, self.buf.numel()
+
+
+_default_ws = Workspace()
+
+
+def _ws_for(op, layer, device, ws, batch=0):
+    need = dd_workspace_bytes(op, layer, batch)
+    buf, n = (ws or _default_ws).get(need, device)
+    return _ptr(buf), n
+
+
+def dd_fwd(X, offsets, values, out_features, Y=None, algo=DD_ALGO_AUTO, ws=None, stream=None):
+    """Y = X . W_K.  X [T x M], offsets int32 [K], values [K x min(M,N)] -> Y [T x N]."""
+    T, M = X.shape
+    N = int(out_features)
+    K = offsets.shape[0]
+    layer = make_layer(T, M, N, K, X.dtype, algo)
+    _dev(X, X.dtype, (T, M), "X")
+    _dev(offsets, torch.int32, (K,), "offsets")
+    _dev(values, X.dtype, (K, min(M, N)), "values")
+    if Y is None:
+        Y = torch.empty((T, N), dtype=X.dtype, device=X.device)
+    _dev(Y, X.dtype, (T, N), "Y")
+    wp, wn = _ws_for(DD_OP_FWD, layer, X.device, ws)
+    _check(load_library().dd_fwd(ctypes.byref(layer), _ptr(X), _ptr(offsets), _ptr(values), _ptr(Y), wp, wn,
+                                 _stream(stream)))
+    return Y
+
+
+def dd_bwd_input(dY, offsets, values, in_features, dX=None, algo=DD_ALGO_AUTO, ws=None, stream=None):
+    """dX = dY . W_K^T.  dY [T x N] -> dX [T x M]."""
+    T, N = dY.shape
+    M = int(in_features)
+    K = offsets.shape[0]
+    layer = make_layer(T, M, N, K, dY.dtype, algo)
+    _dev(dY, dY.dtype, (T, N), "dY")
+    _dev(offsets, torch.int32, (K,), "offsets")
+    _dev(values, dY.dtype, (K, min(M, N)), "values")
+    if dX is None:
+        dX = torch.empty((T, M), dtype=dY.dtype, device=dY.device)
+    _dev(dX, dY.dtype, (T, M), "dX")
+    wp, wn = _ws_for(DD_OP_BWD_INPUT, layer, dY.device, ws)
+    _check(load_library().dd_bwd_input(ctypes.byref(layer), _ptr(dY), _ptr(offsets), _ptr(values), _ptr(dX), wp, wn,
+                                       _stream(stream)))
+    return dX
+
+
+def dd_bwd_weight(X, dY, offsets, dValues=None, algo=DD_ALGO_AUTO, ws=None, stream=None):
+    """dValues [K x min(M,N)] fp32: the gradient of the values on the K diagonals."""
+    T, M = X.shape
+    N = dY.shape[1]
+    K = offsets.shape[0]
+    layer = make_layer(T, M, N, K, X.dtype, algo)
+    _dev(X, X.dtype, (T, M), "X")
+    _dev(dY, X.dtype, (T, N), "dY")
+    _dev(offsets, torch.int32, (K,), "offsets")
+    if dValues is None:
+        dValues = torch.empty((K, min(M, N)), dtype=torch.float32, device=X.device)
+    _dev(dValues, torch.float32, (K, min(M, N)), "dValues")
+    wp, wn = _ws_for(DD_OP_BWD_WEIGHT, layer, X.device, ws)
+    _check(load_library().dd_bwd_weight(ctypes.byref(layer), _ptr(X), _ptr(dY), _ptr(offsets), _ptr(dValues), wp, wn,
+                                        _stream(stream)))
+    return dValues
+
+
+def dd_select_diagonals(scores, K, offsets_out=None, ws=None, stream=None):
+    """Indices of the K largest scores of each row of scores [batch x D], ascending, int32 [batch x K]."""
+    if scores.dim() != 2:
+        raise ValueError("scores must be [batch x D]")
+    B, D = scores.shape
+    _dev(scores, torch.float32, (B, D), "scores")
+    if offsets_out is None:
+        offsets_out = torch.empty((B, K), dtype=torch.int32, device=scores.device)
+    _dev(offsets_out, torch.int32, (B, K), "offsets_out")
+    layer = make_layer(0, D, D, K, DD_F32)
+    wp, wn = _ws_for(DD_OP_SELECT, layer, scores.device, ws, batch=B)
+    _check(load_library().dd_select_diagonals(B, D, int(K), _ptr(scores), _ptr(offsets_out), wp, wn, _stream(stream)))
+    return offsets_out

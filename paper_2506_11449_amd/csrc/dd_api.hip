@@ -1,0 +1,157 @@
+// C ABI of the diagonally-sparse layer: argument checks, reduction of the four products to the
+// two gather shapes (Appendix A: the transpose of a diagonal-sparse matrix is diagonal-sparse
+// with the same starts, so forward and backward-input share kernels), and kernel dispatch.
+#include "../../include/dynadiag.h"
+
+#include "dd_launch.h"
+
+namespace {
+
+constexpr int kMaxFeatures = 65535;
+constexpr size_t kWsAlign = 256;
+
+struct Shape {
+    int D, L;
+    bool expanding;  // M <= N (square included): the diagonal position p is the row of W
+};
+
+dd_status check_layer(const dd_layer *l, Shape *s)
+{
+    if (!l) return DD_ERR_INVALID_ARG;
+    if (l->tokens < 0 || l->in_features < 1 || l->out_features < 1 || l->K < 1) return DD_ERR_INVALID_ARG;
+    if (l->dtype != DD_F32 && l->dtype != DD_BF16) return DD_ERR_INVALID_ARG;
+    if (l->algo != DD_ALGO_AUTO && l->algo != DD_ALGO_VECTOR && l->algo != DD_ALGO_MATRIX) return DD_ERR_INVALID_ARG;
+    const int D = l->in_features > l->out_features ? l->in_features : l->out_features;
+    const int L = l->in_features < l->out_features ? l->in_features : l->out_features;
+    if (l->K > D) return DD_ERR_INVALID_ARG;
+    if (D > kMaxFeatures) return DD_ERR_UNSUPPORTED;
+    s->D = D;
+    s->L = L;
+    s->expanding = l->in_features <= l->out_features;
+    return DD_OK;
+}
+
+dd_status check_ws(const void *ws, size_t ws_bytes, size_t need)
+{
+    if (need == 0) return DD_OK;
+    if (!ws || ws_bytes < need) return DD_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(ws) % kWsAlign) return DD_ERR_WORKSPACE;
+    return DD_OK;
+}
+
+size_t select_ws_bytes(int32_t, int32_t, int32_t) { return 0; }
+
+dd_status product(const dd_layer *l, const Shape &s, bool transposed, const void *src, const int32_t *offsets,
+                  const void *values, void *dst, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!offsets || !values) return DD_ERR_INVALID_ARG;
+    if (l->tokens > 0 && (!src || !dst)) return DD_ERR_INVALID_ARG;
+    const size_t need = dd_workspace_bytes(transposed ? DD_OP_BWD_INPUT : DD_OP_FWD, l, 0);
+    if (dd_status st = check_ws(ws, ws_bytes, need)) return st;
+    if (l->tokens == 0) return DD_OK;
+    if (l->algo == DD_ALGO_MATRIX) return DD_ERR_UNSUPPORTED;
+    dd::ProductArgs a;
+    a.T = l->tokens;
+    a.D = s.D;
+    a.L = s.L;
+    a.K = l->K;
+    a.bf16 = l->dtype == DD_BF16;
+    // forward reads the short side when the layer expands; backward-input is the mirror image
+    a.masked = transposed ? !s.expanding : s.expanding;
+    a.src = src;
+    a.offsets = offsets;
+    a.values = values;
+    a.dst = dst;
+    return dd::launch_product_vector(a, static_cast<hipStream_t>(stream)) == hipSuccess ? DD_OK : DD_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t dd_workspace_bytes(int op, const dd_layer *layer, int32_t batch)
+{
+    if (op == DD_OP_SELECT) {
+        if (!layer) return 0;
+        return select_ws_bytes(batch, layer->in_features, layer->K);
+    }
+    Shape s;
+    if (check_layer(layer, &s) != DD_OK) return 0;
+    switch (op) {
+    case DD_OP_FWD:
+    case DD_OP_BWD_INPUT:
+        return 0;
+    case DD_OP_BWD_WEIGHT:
+        return dd::weight_grad_vector_ws_bytes(layer->tokens, s.D, s.L, layer->K);
+    default:
+        return 0;
+    }
+}
+
+dd_status dd_fwd(const dd_layer *layer, const void *X, const int32_t *offsets, const void *values, void *Y, void *ws,
+                 size_t ws_bytes, void *hip_stream)
+{
+    Shape s;
+    if (dd_status st = check_layer(layer, &s)) return st;
+    return product(layer, s, false, X, offsets, values, Y, ws, ws_bytes, hip_stream);
+}
+
+dd_status dd_bwd_input(const dd_layer *layer, const void *dY, const int32_t *offsets, const void *values, void *dX,
+                       void *ws, size_t ws_bytes, void *hip_stream)
+{
+    Shape s;
+    if (dd_status st = check_layer(layer, &s)) return st;
+    return product(layer, s, true, dY, offsets, values, dX, ws, ws_bytes, hip_stream);
+}
+
+dd_status dd_bwd_weight(const dd_layer *layer, const void *X, const void *dY, const int32_t *offsets, float *dValues,
+                        void *ws, size_t ws_bytes, void *hip_stream)
+{
+    Shape s;
+    if (dd_status st = check_layer(layer, &s)) return st;
+    if (!offsets || !dValues) return DD_ERR_INVALID_ARG;
+    if (layer->tokens > 0 && (!X || !dY)) return DD_ERR_INVALID_ARG;
+    if (dd_status st = check_ws(ws, ws_bytes, dd_workspace_bytes(DD_OP_BWD_WEIGHT, layer, 0))) return st;
+    if (layer->algo == DD_ALGO_MATRIX) return DD_ERR_UNSUPPORTED;
+    dd::WeightGradArgs a;
+    a.T = layer->tokens;
+    a.D = s.D;
+    a.L = s.L;
+    a.K = layer->K;
+    a.bf16 = layer->dtype == DD_BF16;
+    // the short side supplies the unshifted operand, the long side the shifted one
+    a.A = s.expanding ? X : dY;
+    a.B = s.expanding ? dY : X;
+    a.offsets = offsets;
+    a.dValues = dValues;
+    a.ws = ws;
+    return dd::launch_weight_grad_vector(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? DD_OK : DD_ERR_HIP;
+}
+
+dd_status dd_select_diagonals(int32_t batch, int32_t D, int32_t K, const float *scores, int32_t *offsets_out, void *ws,
+                              size_t ws_bytes, void *hip_stream)
+{
+    (void)ws;
+    (void)ws_bytes;
+    if (batch < 0 || D < 1 || K < 1 || K > D) return DD_ERR_INVALID_ARG;
+    if (D > 65536) return DD_ERR_UNSUPPORTED;
+    if (batch == 0) return DD_OK;
+    if (!scores || !offsets_out) return DD_ERR_INVALID_ARG;
+    return dd::launch_select(batch, D, K, scores, offsets_out, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? DD_OK
+               : DD_ERR_HIP;
+}
+
+const char *dd_status_string(dd_status status)
+{
+    switch (status) {
+    case DD_OK: return "ok";
+    case DD_ERR_INVALID_ARG: return "invalid argument";
+    case DD_ERR_UNSUPPORTED: return "unsupported size or algorithm";
+    case DD_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case DD_ERR_HIP: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

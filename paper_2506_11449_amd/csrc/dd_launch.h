@@ -1,0 +1,42 @@
+// Host-side launchers, one per kernel family.  Arguments are already validated by the C ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace dd {
+
+// The two product shapes every forward / backward-input call reduces to
+// (D = long side, L = short side, offsets taken modulo D):
+//   gather:        dst[t, p] = sum_k src[t, (p + o_k) mod D] * v_k[p]              src [T x D], dst [T x L]
+//   masked gather: dst[t, q] = sum_{k : c < L} src[t, c] * v_k[c], c = (q - o_k) mod D   src [T x L], dst [T x D]
+struct ProductArgs {
+    int64_t T;
+    int D, L, K;
+    bool bf16;
+    bool masked;          // false: gather, true: masked gather
+    const void *src;
+    const int32_t *offsets;
+    const void *values;   // [K x L]
+    void *dst;
+};
+
+// dV[k][p] = sum_t A[t, p] * B[t, (p + o_k) mod D];  A [T x L] (short side), B [T x D] (long side)
+struct WeightGradArgs {
+    int64_t T;
+    int D, L, K;
+    bool bf16;
+    const void *A;
+    const void *B;
+    const int32_t *offsets;
+    float *dValues;       // [K x L]
+    void *ws;
+};
+
+hipError_t launch_product_vector(const ProductArgs &a, hipStream_t stream);
+size_t weight_grad_vector_ws_bytes(int64_t T, int D, int L, int K);
+hipError_t launch_weight_grad_vector(const WeightGradArgs &a, hipStream_t stream);
+
+hipError_t launch_select(int batch, int D, int K, const float *scores, int *out, hipStream_t stream);
+
+}  // namespace dd

@@ -1,0 +1,209 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle, element by element on
+small seeded cases (several tiles plus ragged tails, all edge cases), and on sampled outputs
+at the full benchmark sizes."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2506_11449_amd as dd
+from oracle import dd_oracle as orc
+from paper_2506_11449_amd import synth
+from tests.parity_util import ALGOS, TOL, TOL_DV, random_case, rel_err, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+# (M, N, K, T): squares, both rectangular orientations, widths that are no multiple of 64,
+# token counts that are no multiple of any tile.
+SMALL = [
+    (64, 64, 8, 16),
+    (48, 48, 5, 33),
+    (100, 100, 13, 70),
+    (768, 768, 77, 300),
+    (64, 192, 20, 50),
+    (192, 64, 20, 50),
+    (100, 260, 31, 129),
+    (260, 100, 31, 129),
+    (768, 3072, 307, 130),
+    (3072, 768, 307, 130),
+    (1024, 1024, 51, 257),
+    (33, 7, 4, 19),
+    (7, 33, 4, 19),
+    (1, 1, 1, 5),
+    (300, 300, 300, 65),
+]
+
+
+def run_all(offsets, values, X, dY, dtype, algo):
+    T, M = X.shape
+    N = dY.shape[1]
+    d_off = torch.from_numpy(np.asarray(offsets, dtype=np.int32)).cuda()
+    d_val, d_X, d_dY = to_dev(values, dtype), to_dev(X, dtype), to_dev(dY, dtype)
+    Y = dd.dd_fwd(d_X, d_off, d_val, N, algo=algo)
+    dX = dd.dd_bwd_input(d_dY, d_off, d_val, M, algo=algo)
+    dV = dd.dd_bwd_weight(d_X, d_dY, d_off, algo=algo)
+    torch.cuda.synchronize()
+    return to_host(Y), to_host(dX), to_host(dV)
+
+
+def check_against_oracle(offsets, values, X, dY, dtype, algo):
+    M, N = X.shape[1], dY.shape[1]
+    Y, dX, dV = run_all(offsets, values, X, dY, dtype, algo)
+    assert rel_err(Y, orc.fwd(X, offsets, values, N)) <= TOL[dtype]
+    assert rel_err(dX, orc.bwd_input(dY, offsets, values, M)) <= TOL[dtype]
+    assert rel_err(dV, orc.bwd_weight(X, dY, offsets)) <= TOL_DV
+
+
+@pytest.mark.parametrize("algo", ["vector"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("M,N,K,T", SMALL)
+def test_small_cases_elementwise(M, N, K, T, dtype, algo):
+    offsets, values, X, dY = random_case(M, N, K, T, dtype, seed=1000 * M + 10 * N + K)
+    check_against_oracle(offsets, values, X, dY, dtype, ALGOS[algo])
+
+
+@pytest.mark.parametrize("algo", ["vector"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_tiny_config(dtype, algo):
+    layer = synth.WORKLOADS["tiny"][0]
+    offsets, values, X, dY = synth.layer_inputs(layer, seed=2506)
+    if dtype == "bf16":
+        values, X, dY = map(synth.round_to_bf16, (values, X, dY))
+    check_against_oracle(offsets, values, X, dY, dtype, ALGOS[algo])
+
+
+@pytest.mark.parametrize("algo", ["vector"])
+@pytest.mark.parametrize("M,N", [(96, 96), (40, 136), (136, 40)])
+def test_offset_edge_cases(M, N, algo):
+    D = max(M, N)
+    cases = {
+        "single_main": [0],
+        "single_last": [D - 1],
+        "negative": [-1, -D, -D - 3, 2 * D + 5],
+        "duplicates": [3, 3, 3, 17],
+        "unsorted": [50, 2, 31, 7, 90 % D],
+        "adjacent_run": list(range(10, 26)),
+    }
+    for name, offs in cases.items():
+        for dtype in ("f32", "bf16"):
+            offsets, values, X, dY = random_case(M, N, len(offs), 37, dtype, seed=len(name) + M, offsets=offs)
+            check_against_oracle(offsets, values, X, dY, dtype, ALGOS[algo])
+
+
+@pytest.mark.parametrize("algo", ["vector"])
+def test_all_diagonals_is_dense(algo):
+    for M, N in ((64, 64), (32, 80), (80, 32)):
+        D = max(M, N)
+        offsets, values, X, dY = random_case(M, N, D, 21, "f32", seed=D, offsets=np.arange(D))
+        check_against_oracle(offsets, values, X, dY, "f32", ALGOS[algo])
+
+
+@pytest.mark.parametrize("algo", ["vector"])
+def test_identity_and_shift(algo):
+    """Offset o with all-ones values moves column i to column (i + o) mod n, exactly."""
+    X = np.random.default_rng(1).standard_normal((9, 128)).astype(np.float32)
+    ones = torch.ones((1, 128), device="cuda")
+    for o in (0, 1, 127, -5):
+        off = torch.tensor([o], dtype=torch.int32, device="cuda")
+        Y = dd.dd_fwd(torch.from_numpy(X).cuda(), off, ones, 128, algo=ALGOS[algo])
+        np.testing.assert_array_equal(Y.cpu().numpy(), np.roll(X, o, axis=1))
+
+
+@pytest.mark.parametrize("algo", ["vector"])
+def test_zero_tokens(algo):
+    off = torch.tensor([1, 5], dtype=torch.int32, device="cuda")
+    val = torch.ones((2, 16), device="cuda")
+    X = torch.empty((0, 16), device="cuda")
+    assert dd.dd_fwd(X, off, val, 16, algo=ALGOS[algo]).shape == (0, 16)
+    assert dd.dd_bwd_input(X, off, val, 16, algo=ALGOS[algo]).shape == (0, 16)
+    dV = dd.dd_bwd_weight(X, X, off, algo=ALGOS[algo])
+    assert torch.count_nonzero(dV).item() == 0
+
+
+@pytest.mark.parametrize("algo", ["vector"])
+def test_weight_gradient_is_deterministic(algo):
+    offsets, values, X, dY = random_case(256, 256, 26, 5000, "bf16", seed=77)
+    d_off = torch.from_numpy(offsets).cuda()
+    d_X, d_dY = to_dev(X, "bf16"), to_dev(dY, "bf16")
+    a = dd.dd_bwd_weight(d_X, d_dY, d_off, algo=ALGOS[algo]).clone()
+    b = dd.dd_bwd_weight(d_X, d_dY, d_off, algo=ALGOS[algo])
+    assert torch.equal(a, b)
+
+
+# ---- full benchmark sizes, in the launch configuration bench.py times ----
+
+@pytest.mark.parametrize("algo", ["vector"])
+def test_vitb_attention_projection_full(algo):
+    """ViT-Base attention projection, 768x768, 90 % sparse, 12608 tokens, bf16: every element."""
+    layer = synth.WORKLOADS["vitb_attn_proj"][0]
+    offsets, values, X, dY = synth.layer_inputs(layer, seed=2506)
+    check_against_oracle(offsets, values, X, dY, "bf16", ALGOS[algo])
+
+
+def _sampled_check(layer, seed, algo, n_rows=48, n_entries=256):
+    offsets, values, X, dY = synth.layer_inputs(layer, seed)
+    M, N = layer.in_features, layer.out_features
+    Y, dX, dV = run_all(offsets, values, X, dY, layer.dtype, algo)
+    rng = np.random.default_rng(seed)
+    rows = np.unique(np.concatenate([[0, layer.tokens - 1], rng.integers(0, layer.tokens, n_rows)]))
+    # token rows are independent: the oracle on a subset of rows gives those rows of the full result
+    assert rel_err(Y[rows], orc.fwd(X[rows], offsets, values, N)) <= TOL[layer.dtype]
+    assert rel_err(dX[rows], orc.bwd_input(dY[rows], offsets, values, M)) <= TOL[layer.dtype]
+    ks = rng.integers(0, layer.K, n_entries)
+    ps = rng.integers(0, layer.L, n_entries)
+    ks[:2], ps[:2] = [0, layer.K - 1], [0, layer.L - 1]
+    ref = orc.bwd_weight_sampled(X, dY, offsets, ks, ps)
+    assert rel_err(dV[ks, ps], ref) <= TOL_DV
+    assert np.all(np.isfinite(Y)) and np.all(np.isfinite(dX)) and np.all(np.isfinite(dV))
+
+
+@pytest.mark.parametrize("algo", ["vector"])
+@pytest.mark.parametrize("which", [0, 1])
+def test_vitb_mlp_sampled(which, algo):
+    _sampled_check(synth.WORKLOADS["vitb_mlp"][which], 2506 + which, ALGOS[algo])
+
+
+@pytest.mark.parametrize("algo", ["vector"])
+@pytest.mark.parametrize("name", ["vitl_1024x1024_s80", "vitl_1024x1024_s95", "vitl_1024x4096_s90",
+                                  "vitl_4096x1024_s90"])
+def test_vitl_sampled(name, algo):
+    layer = next(l for l in synth.WORKLOADS["vitl"] if l.name == name)
+    _sampled_check(layer, 4096, ALGOS[algo], n_rows=24, n_entries=128)
+
+
+# ---- selection: bit-exact ----
+
+def _select_check(scores, K):
+    got = dd.dd_select_diagonals(torch.from_numpy(scores).cuda(), K).cpu().numpy()
+    np.testing.assert_array_equal(got, orc.select(scores, K))
+
+
+def test_select_matches_oracle_bit_exactly():
+    for D, K, B in ((64, 8, 1), (768, 77, 48), (3072, 307, 24), (1024, 51, 3), (4096, 819, 3), (1000, 1, 2),
+                    (100, 100, 2), (65536, 6000, 1), (5, 3, 7)):
+        _select_check(synth.draw_scores(B, D, seed=D + K), K)
+
+
+def test_select_ties_nan_and_signed_zero():
+    rng = np.random.default_rng(5)
+    q = (np.round(rng.standard_normal((6, 777)) * 2) / 2).astype(np.float32)  # tie-heavy
+    q[q == 0] = np.where(rng.random(np.count_nonzero(q == 0)) < 0.5, -0.0, 0.0)
+    for K in (1, 50, 400, 777):
+        _select_check(q, K)
+    s = rng.standard_normal((4, 300)).astype(np.float32)
+    s[:, ::7] = np.nan
+    s[1, :] = np.nan
+    s[2, 5] = np.inf
+    s[2, 6] = -np.inf
+    for K in (1, 40, 280, 300):
+        _select_check(s, K)
+    _select_check(np.zeros((2, 130), np.float32), 17)
+
+
+def test_select_feeds_forward_without_leaving_the_device():
+    layer = synth.WORKLOADS["tiny"][0]
+    _, values, X, _ = synth.layer_inputs(layer, seed=9)
+    scores = synth.draw_scores(1, layer.D, seed=9)
+    d_off = dd.dd_select_diagonals(torch.from_numpy(scores).cuda(), layer.K)
+    Y = dd.dd_fwd(to_dev(X, "f32"), d_off[0], to_dev(values, "f32"), layer.out_features)
+    ref = orc.fwd(X, orc.select(scores, layer.K)[0], values, layer.out_features)
+    assert rel_err(to_host(Y), ref) <= TOL["f32"]
