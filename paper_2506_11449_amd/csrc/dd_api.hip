@@ -41,6 +41,18 @@ dd_status check_ws(const void *ws, size_t ws_bytes, size_t need)
 
 size_t select_ws_bytes(int32_t, int32_t, int32_t) { return 0; }
 
+bool aligned16(const void *p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
+
+// Does the shape allow the matrix-core kernels, and does the request (or the density) ask for them?
+// Below a density K/D of about 1/48 visiting only the stored weights on the vector ALUs is cheaper
+// than a dense contraction on the matrix cores (their rates differ by 32x, less what tiling loses).
+bool wants_matrix(const dd_layer *l, const Shape &s)
+{
+    if (l->algo == DD_ALGO_VECTOR) return false;
+    if (!dd::product_matrix_supported(l->tokens, s.D, s.L, l->dtype == DD_BF16)) return false;
+    return l->algo == DD_ALGO_MATRIX || int64_t(l->K) * 48 >= s.D;
+}
+
 dd_status product(const dd_layer *l, const Shape &s, bool transposed, const void *src, const int32_t *offsets,
                   const void *values, void *dst, void *ws, size_t ws_bytes, void *stream)
 {
@@ -49,7 +61,9 @@ dd_status product(const dd_layer *l, const Shape &s, bool transposed, const void
     const size_t need = dd_workspace_bytes(transposed ? DD_OP_BWD_INPUT : DD_OP_FWD, l, 0);
     if (dd_status st = check_ws(ws, ws_bytes, need)) return st;
     if (l->tokens == 0) return DD_OK;
-    if (l->algo == DD_ALGO_MATRIX) return DD_ERR_UNSUPPORTED;
+    bool matrix = wants_matrix(l, s);
+    if (matrix && !(aligned16(src) && aligned16(dst))) matrix = false;  // 16-byte vector accesses
+    if (l->algo == DD_ALGO_MATRIX && !matrix) return DD_ERR_UNSUPPORTED;
     dd::ProductArgs a;
     a.T = l->tokens;
     a.D = s.D;
@@ -62,7 +76,10 @@ dd_status product(const dd_layer *l, const Shape &s, bool transposed, const void
     a.offsets = offsets;
     a.values = values;
     a.dst = dst;
-    return dd::launch_product_vector(a, static_cast<hipStream_t>(stream)) == hipSuccess ? DD_OK : DD_ERR_HIP;
+    a.ws = ws;
+    const hipError_t e = matrix ? dd::launch_product_matrix(a, static_cast<hipStream_t>(stream))
+                                : dd::launch_product_vector(a, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? DD_OK : DD_ERR_HIP;
 }
 
 }  // namespace
@@ -80,7 +97,7 @@ size_t dd_workspace_bytes(int op, const dd_layer *layer, int32_t batch)
     switch (op) {
     case DD_OP_FWD:
     case DD_OP_BWD_INPUT:
-        return 0;
+        return wants_matrix(layer, s) ? dd::product_matrix_ws_bytes(s.D, s.L) : 0;
     case DD_OP_BWD_WEIGHT:
         return dd::weight_grad_vector_ws_bytes(layer->tokens, s.D, s.L, layer->K);
     default:

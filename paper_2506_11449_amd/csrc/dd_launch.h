@@ -19,6 +19,7 @@ struct ProductArgs {
     const int32_t *offsets;
     const void *values;   // [K x L]
     void *dst;
+    void *ws;             // scratch of the size the chosen kernel family asks for
 };
 
 // dV[k][p] = sum_t A[t, p] * B[t, (p + o_k) mod D];  A [T x L] (short side), B [T x D] (long side)
@@ -34,6 +35,11 @@ struct WeightGradArgs {
 };
 
 hipError_t launch_product_vector(const ProductArgs &a, hipStream_t stream);
+
+// matrix-core family (bf16 only, feature counts multiples of 128)
+bool product_matrix_supported(int64_t T, int D, int L, bool bf16);
+size_t product_matrix_ws_bytes(int D, int L);
+hipError_t launch_product_matrix(const ProductArgs &a, hipStream_t stream);
 size_t weight_grad_vector_ws_bytes(int64_t T, int D, int L, int K);
 hipError_t launch_weight_grad_vector(const WeightGradArgs &a, hipStream_t stream);
 

@@ -26,6 +26,10 @@ SMALL = [
     (768, 3072, 307, 130),
     (3072, 768, 307, 130),
     (1024, 1024, 51, 257),
+    (128, 128, 13, 1),
+    (256, 128, 26, 161),
+    (128, 384, 40, 415),
+    (512, 512, 3, 700),
     (33, 7, 4, 19),
     (7, 33, 4, 19),
     (1, 1, 1, 5),
@@ -33,27 +37,50 @@ SMALL = [
 ]
 
 
+def matrix_shape_ok(M, N, dtype):
+    """Shapes the matrix-core kernels cover: bf16 storage, both feature counts multiples of 128."""
+    return dtype == "bf16" and M % 128 == 0 and N % 128 == 0 and max(M, N) <= 8192
+
+
+def _call(fn, *args, algo):
+    """Run one entry point; a forced kernel family that does not cover the case must say so."""
+    try:
+        return fn(*args, algo=algo)
+    except dd.DynaDiagError as e:
+        if algo != dd.DD_ALGO_AUTO and e.status == 2:
+            return None
+        raise
+
+
 def run_all(offsets, values, X, dY, dtype, algo):
     T, M = X.shape
     N = dY.shape[1]
     d_off = torch.from_numpy(np.asarray(offsets, dtype=np.int32)).cuda()
     d_val, d_X, d_dY = to_dev(values, dtype), to_dev(X, dtype), to_dev(dY, dtype)
-    Y = dd.dd_fwd(d_X, d_off, d_val, N, algo=algo)
-    dX = dd.dd_bwd_input(d_dY, d_off, d_val, M, algo=algo)
-    dV = dd.dd_bwd_weight(d_X, d_dY, d_off, algo=algo)
+    Y = _call(dd.dd_fwd, d_X, d_off, d_val, N, algo=algo)
+    dX = _call(dd.dd_bwd_input, d_dY, d_off, d_val, M, algo=algo)
+    dV = _call(dd.dd_bwd_weight, d_X, d_dY, d_off, algo=algo)
     torch.cuda.synchronize()
-    return to_host(Y), to_host(dX), to_host(dV)
+    if algo == dd.DD_ALGO_MATRIX:
+        ok = matrix_shape_ok(M, N, dtype) and T > 0
+        assert (Y is not None) == ok and (dX is not None) == ok
+    else:
+        assert Y is not None and dX is not None and dV is not None
+    return tuple(None if r is None else to_host(r) for r in (Y, dX, dV))
 
 
 def check_against_oracle(offsets, values, X, dY, dtype, algo):
     M, N = X.shape[1], dY.shape[1]
     Y, dX, dV = run_all(offsets, values, X, dY, dtype, algo)
-    assert rel_err(Y, orc.fwd(X, offsets, values, N)) <= TOL[dtype]
-    assert rel_err(dX, orc.bwd_input(dY, offsets, values, M)) <= TOL[dtype]
-    assert rel_err(dV, orc.bwd_weight(X, dY, offsets)) <= TOL_DV
+    if Y is not None:
+        assert rel_err(Y, orc.fwd(X, offsets, values, N)) <= TOL[dtype]
+    if dX is not None:
+        assert rel_err(dX, orc.bwd_input(dY, offsets, values, M)) <= TOL[dtype]
+    if dV is not None:
+        assert rel_err(dV, orc.bwd_weight(X, dY, offsets)) <= TOL_DV
 
 
-@pytest.mark.parametrize("algo", ["vector"])
+@pytest.mark.parametrize("algo", ["vector", "matrix", "auto"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("M,N,K,T", SMALL)
 def test_small_cases_elementwise(M, N, K, T, dtype, algo):
@@ -61,7 +88,7 @@ def test_small_cases_elementwise(M, N, K, T, dtype, algo):
     check_against_oracle(offsets, values, X, dY, dtype, ALGOS[algo])
 
 
-@pytest.mark.parametrize("algo", ["vector"])
+@pytest.mark.parametrize("algo", ["vector", "matrix", "auto"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_tiny_config(dtype, algo):
     layer = synth.WORKLOADS["tiny"][0]
@@ -71,7 +98,7 @@ def test_tiny_config(dtype, algo):
     check_against_oracle(offsets, values, X, dY, dtype, ALGOS[algo])
 
 
-@pytest.mark.parametrize("algo", ["vector"])
+@pytest.mark.parametrize("algo", ["vector", "matrix", "auto"])
 @pytest.mark.parametrize("M,N", [(96, 96), (40, 136), (136, 40)])
 def test_offset_edge_cases(M, N, algo):
     D = max(M, N)
@@ -89,7 +116,7 @@ def test_offset_edge_cases(M, N, algo):
             check_against_oracle(offsets, values, X, dY, dtype, ALGOS[algo])
 
 
-@pytest.mark.parametrize("algo", ["vector"])
+@pytest.mark.parametrize("algo", ["vector", "matrix", "auto"])
 def test_all_diagonals_is_dense(algo):
     for M, N in ((64, 64), (32, 80), (80, 32)):
         D = max(M, N)
@@ -97,41 +124,51 @@ def test_all_diagonals_is_dense(algo):
         check_against_oracle(offsets, values, X, dY, "f32", ALGOS[algo])
 
 
-@pytest.mark.parametrize("algo", ["vector"])
-def test_identity_and_shift(algo):
+@pytest.mark.parametrize("algo", ["vector", "matrix", "auto"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_identity_and_shift(dtype, algo):
     """Offset o with all-ones values moves column i to column (i + o) mod n, exactly."""
     X = np.random.default_rng(1).standard_normal((9, 128)).astype(np.float32)
-    ones = torch.ones((1, 128), device="cuda")
+    if dtype == "bf16":
+        X = synth.round_to_bf16(X)
+    ones = to_dev(np.ones((1, 128), np.float32), dtype)
     for o in (0, 1, 127, -5):
         off = torch.tensor([o], dtype=torch.int32, device="cuda")
-        Y = dd.dd_fwd(torch.from_numpy(X).cuda(), off, ones, 128, algo=ALGOS[algo])
-        np.testing.assert_array_equal(Y.cpu().numpy(), np.roll(X, o, axis=1))
+        Y = _call(dd.dd_fwd, to_dev(X, dtype), off, ones, 128, algo=ALGOS[algo])
+        if Y is None:
+            assert algo == "matrix" and dtype == "f32"
+            continue
+        np.testing.assert_array_equal(to_host(Y), np.roll(X, o, axis=1).astype(np.float64))
 
 
-@pytest.mark.parametrize("algo", ["vector"])
+@pytest.mark.parametrize("algo", ["vector", "matrix", "auto"])
 def test_zero_tokens(algo):
     off = torch.tensor([1, 5], dtype=torch.int32, device="cuda")
     val = torch.ones((2, 16), device="cuda")
     X = torch.empty((0, 16), device="cuda")
     assert dd.dd_fwd(X, off, val, 16, algo=ALGOS[algo]).shape == (0, 16)
     assert dd.dd_bwd_input(X, off, val, 16, algo=ALGOS[algo]).shape == (0, 16)
-    dV = dd.dd_bwd_weight(X, X, off, algo=ALGOS[algo])
-    assert torch.count_nonzero(dV).item() == 0
+    dV = _call(dd.dd_bwd_weight, X, X, off, algo=ALGOS[algo])
+    if dV is not None:
+        assert torch.count_nonzero(dV).item() == 0
 
 
-@pytest.mark.parametrize("algo", ["vector"])
+@pytest.mark.parametrize("algo", ["vector", "matrix", "auto"])
 def test_weight_gradient_is_deterministic(algo):
     offsets, values, X, dY = random_case(256, 256, 26, 5000, "bf16", seed=77)
     d_off = torch.from_numpy(offsets).cuda()
     d_X, d_dY = to_dev(X, "bf16"), to_dev(dY, "bf16")
-    a = dd.dd_bwd_weight(d_X, d_dY, d_off, algo=ALGOS[algo]).clone()
+    a = _call(dd.dd_bwd_weight, d_X, d_dY, d_off, algo=ALGOS[algo])
+    if a is None:
+        pytest.skip("this kernel family has no weight-gradient kernel for the shape")
+    a = a.clone()
     b = dd.dd_bwd_weight(d_X, d_dY, d_off, algo=ALGOS[algo])
     assert torch.equal(a, b)
 
 
 # ---- full benchmark sizes, in the launch configuration bench.py times ----
 
-@pytest.mark.parametrize("algo", ["vector"])
+@pytest.mark.parametrize("algo", ["vector", "matrix", "auto"])
 def test_vitb_attention_projection_full(algo):
     """ViT-Base attention projection, 768x768, 90 % sparse, 12608 tokens, bf16: every element."""
     layer = synth.WORKLOADS["vitb_attn_proj"][0]
@@ -143,6 +180,7 @@ def _sampled_check(layer, seed, algo, n_rows=48, n_entries=256):
     offsets, values, X, dY = synth.layer_inputs(layer, seed)
     M, N = layer.in_features, layer.out_features
     Y, dX, dV = run_all(offsets, values, X, dY, layer.dtype, algo)
+    assert Y is not None and dX is not None
     rng = np.random.default_rng(seed)
     rows = np.unique(np.concatenate([[0, layer.tokens - 1], rng.integers(0, layer.tokens, n_rows)]))
     # token rows are independent: the oracle on a subset of rows gives those rows of the full result
@@ -151,18 +189,20 @@ def _sampled_check(layer, seed, algo, n_rows=48, n_entries=256):
     ks = rng.integers(0, layer.K, n_entries)
     ps = rng.integers(0, layer.L, n_entries)
     ks[:2], ps[:2] = [0, layer.K - 1], [0, layer.L - 1]
-    ref = orc.bwd_weight_sampled(X, dY, offsets, ks, ps)
-    assert rel_err(dV[ks, ps], ref) <= TOL_DV
-    assert np.all(np.isfinite(Y)) and np.all(np.isfinite(dX)) and np.all(np.isfinite(dV))
+    assert np.all(np.isfinite(Y)) and np.all(np.isfinite(dX))
+    if dV is not None:
+        ref = orc.bwd_weight_sampled(X, dY, offsets, ks, ps)
+        assert rel_err(dV[ks, ps], ref) <= TOL_DV
+        assert np.all(np.isfinite(dV))
 
 
-@pytest.mark.parametrize("algo", ["vector"])
+@pytest.mark.parametrize("algo", ["vector", "matrix", "auto"])
 @pytest.mark.parametrize("which", [0, 1])
 def test_vitb_mlp_sampled(which, algo):
     _sampled_check(synth.WORKLOADS["vitb_mlp"][which], 2506 + which, ALGOS[algo])
 
 
-@pytest.mark.parametrize("algo", ["vector"])
+@pytest.mark.parametrize("algo", ["vector", "matrix", "auto"])
 @pytest.mark.parametrize("name", ["vitl_1024x1024_s80", "vitl_1024x1024_s95", "vitl_1024x4096_s90",
                                   "vitl_4096x1024_s90"])
 def test_vitl_sampled(name, algo):
