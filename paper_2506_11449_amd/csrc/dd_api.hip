@@ -53,6 +53,13 @@ bool wants_matrix(const dd_layer *l, const Shape &s)
     return l->algo == DD_ALGO_MATRIX || int64_t(l->K) * 48 >= s.D;
 }
 
+bool wants_matrix_wgrad(const dd_layer *l, const Shape &s)
+{
+    if (l->algo == DD_ALGO_VECTOR) return false;
+    if (!dd::weight_grad_matrix_supported(l->tokens, s.D, s.L, l->dtype == DD_BF16)) return false;
+    return l->algo == DD_ALGO_MATRIX || int64_t(l->K) * 48 >= s.D;
+}
+
 dd_status product(const dd_layer *l, const Shape &s, bool transposed, const void *src, const int32_t *offsets,
                   const void *values, void *dst, void *ws, size_t ws_bytes, void *stream)
 {
@@ -99,7 +106,8 @@ size_t dd_workspace_bytes(int op, const dd_layer *layer, int32_t batch)
     case DD_OP_BWD_INPUT:
         return wants_matrix(layer, s) ? dd::product_matrix_ws_bytes(s.D, s.L) : 0;
     case DD_OP_BWD_WEIGHT:
-        return dd::weight_grad_vector_ws_bytes(layer->tokens, s.D, s.L, layer->K);
+        return wants_matrix_wgrad(layer, s) ? dd::weight_grad_matrix_ws_bytes(layer->tokens, s.D, s.L, layer->K)
+                                            : dd::weight_grad_vector_ws_bytes(layer->tokens, s.D, s.L, layer->K);
     default:
         return 0;
     }
@@ -129,7 +137,9 @@ dd_status dd_bwd_weight(const dd_layer *layer, const void *X, const void *dY, co
     if (!offsets || !dValues) return DD_ERR_INVALID_ARG;
     if (layer->tokens > 0 && (!X || !dY)) return DD_ERR_INVALID_ARG;
     if (dd_status st = check_ws(ws, ws_bytes, dd_workspace_bytes(DD_OP_BWD_WEIGHT, layer, 0))) return st;
-    if (layer->algo == DD_ALGO_MATRIX) return DD_ERR_UNSUPPORTED;
+    bool matrix = wants_matrix_wgrad(layer, s);
+    if (matrix && !(aligned16(X) && aligned16(dY))) matrix = false;
+    if (layer->algo == DD_ALGO_MATRIX && !matrix) return DD_ERR_UNSUPPORTED;
     dd::WeightGradArgs a;
     a.T = layer->tokens;
     a.D = s.D;
@@ -142,7 +152,9 @@ dd_status dd_bwd_weight(const dd_layer *layer, const void *X, const void *dY, co
     a.offsets = offsets;
     a.dValues = dValues;
     a.ws = ws;
-    return dd::launch_weight_grad_vector(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? DD_OK : DD_ERR_HIP;
+    const hipError_t e = matrix ? dd::launch_weight_grad_matrix(a, static_cast<hipStream_t>(hip_stream))
+                                : dd::launch_weight_grad_vector(a, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? DD_OK : DD_ERR_HIP;
 }
 
 dd_status dd_select_diagonals(int32_t batch, int32_t D, int32_t K, const float *scores, int32_t *offsets_out, void *ws,

@@ -43,6 +43,11 @@ hipError_t launch_product_matrix(const ProductArgs &a, hipStream_t stream);
 size_t weight_grad_vector_ws_bytes(int64_t T, int D, int L, int K);
 hipError_t launch_weight_grad_vector(const WeightGradArgs &a, hipStream_t stream);
 
+// matrix-core family (bf16 only, short side a multiple of 128, long side a multiple of 256)
+bool weight_grad_matrix_supported(int64_t T, int D, int L, bool bf16);
+size_t weight_grad_matrix_ws_bytes(int64_t T, int D, int L, int K);
+hipError_t launch_weight_grad_matrix(const WeightGradArgs &a, hipStream_t stream);
+
 hipError_t launch_select(int batch, int D, int K, const float *scores, int *out, hipStream_t stream);
 
 }  // namespace dd

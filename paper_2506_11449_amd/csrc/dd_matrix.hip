@@ -6,14 +6,18 @@
 // only the K*L stored weights on the vector ALUs.  HBM traffic is the same either way: X is read
 // once, Y written once; the dense operand (<= a few MB) lives in L2.
 //
-// Step 1 (materialize_kernel): the operand Bt [NC x KD] (one row per output column, contraction
-//   index contiguous) is written from (offsets, values) following Sec. 3.1 Eq. 1-3 / Appendix A.
-// Step 2 (mm_kernel): C [T x NC] = A [T x KD] . Bt^T with v_mfma_f32_32x32x16_bf16.  A workgroup
-//   of four waves owns a BM x BN tile of C; both operands are staged through LDS in 64-wide
-//   k-slices, double buffered; 16-byte chunks are XOR-swizzled so that fragment reads are free of
-//   bank conflicts.  The MFMA rows are output columns and the MFMA columns are tokens, which leaves
-//   every lane with four consecutive output columns of one token, so the tile is transposed back
-//   through LDS once and stored with full-width row segments.
+// Step 1 (materialize_kernel): the dense operand is written from (offsets, values) following
+//   Sec. 3.1 Eq. 1-3 / Appendix A, directly in the register layout of the MFMA "A" operand:
+//   a block of 32 output columns x 16 contraction indices is 1 KB, lane-major, so a wave fetches
+//   a fragment with one fully coalesced 16-byte-per-lane load and the operand never touches LDS.
+// Step 2 (mm_kernel): C [T x NC] = A [T x KD] . W with v_mfma_f32_32x32x16_bf16.  A workgroup of
+//   four waves owns a BM x BN tile of C; each wave owns BN/4 output columns (its weight fragments
+//   are private, loaded global -> registers one k-slice ahead) and all BM tokens.  The token
+//   operand is shared by the four waves and goes through a three-deep LDS ring in 64-wide
+//   k-slices, XOR-swizzled in 16-byte chunks so that fragment reads are free of bank conflicts.
+//   The MFMA rows are output columns and the MFMA columns are tokens, which leaves every lane
+//   with four consecutive output columns of one token, so the tile is transposed back through
+//   LDS once and stored with full-width row segments.
 #include "dd_common.h"
 #include "dd_launch.h"
 
@@ -29,21 +33,29 @@ constexpr int kMmThreads = 256;
 constexpr int kBK = 64;          // contraction extent of one LDS stage: 64 bf16 = 128 bytes per row
 constexpr int kRowBytes = kBK * 2;
 constexpr int kXcds = 8;
+constexpr int kRing = 3;         // LDS stages of the token operand
 
 // position of 16-byte chunk `chunk` (0..7) inside its 128-byte row
 __device__ __forceinline__ int swizzle(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
 
+// Fragment-major layout of the dense operand: element (output column j, contraction index i) of a
+// matrix with KD contraction indices.  Block (j / 32, i / 16) holds 64 lanes x 8 elements; lane
+// (j % 32) + 32 * ((i % 16) / 8) holds elements i % 8 -- the operand layout of the 32x32x16 MFMA.
+__device__ __forceinline__ size_t fragment_index(int j, int i, int KD)
+{
+    return ((size_t(j >> 5) * (KD >> 4) + (i >> 4)) * 64 + (j & 31) + 32 * ((i >> 3) & 1)) * 8 + (i & 7);
+}
+
 // ---------------------------------------------------------------------------------------------
-// Step 1: dense operand from the diagonals.
-//   long_major = 1:  Bt[q][p] = sum_{k: (q - o_k) mod D = p < L} v_k[p]     rows q in [0, D), KD = L
-//   long_major = 0:  Bt[p][q] = sum_{k: (p + o_k) mod D = q} v_k[p]         rows p in [0, L), KD = D
-// One workgroup per row; the row is summed in fp32 in LDS (repeated offsets add, Eq. 3) and
-// rounded to bf16 once.
+// Step 1: dense operand from the diagonals, one workgroup per output column r of the product.
+//   long_major = 1:  row r = q in [0, D), KD = L:  w[p] = sum_{k: (q - o_k) mod D = p < L} v_k[p]
+//   long_major = 0:  row r = p in [0, L), KD = D:  w[q] = sum_{k: (p + o_k) mod D = q} v_k[p]
+// The row is summed in fp32 in LDS (repeated offsets add, Eq. 3) and rounded to bf16 once.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void materialize_kernel(int D, int L, int K, int long_major,
                                                           const int *__restrict__ offsets,
                                                           const uint16_t *__restrict__ values,
-                                                          uint16_t *__restrict__ Bt)
+                                                          uint16_t *__restrict__ Wf)
 {
     extern __shared__ float row[];
     const int r = blockIdx.x;
@@ -63,12 +75,17 @@ __global__ __launch_bounds__(256) void materialize_kernel(int D, int L, int K, i
         }
     }
     __syncthreads();
-    uint16_t *dst = Bt + size_t(r) * KD;
-    for (int c = threadIdx.x; c < KD; c += 256) dst[c] = f32_to_bf16(row[c]);
+    for (int c8 = threadIdx.x; c8 < KD / 8; c8 += 256) {  // 8 consecutive contraction indices = one 16-byte piece
+        u32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            v[e] = uint32_t(f32_to_bf16(row[c8 * 8 + 2 * e])) | (uint32_t(f32_to_bf16(row[c8 * 8 + 2 * e + 1])) << 16);
+        *reinterpret_cast<u32x4 *>(Wf + fragment_index(r, c8 * 8, KD)) = v;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
-// Step 2: C [T x NC] = A [T x KD] . Bt[NC x KD]^T
+// Step 2: C [T x NC] = A [T x KD] . W,  W given fragment-major
 // ---------------------------------------------------------------------------------------------
 template <int BM, int BN>
 struct MmTile {
@@ -76,20 +93,17 @@ struct MmTile {
     static constexpr int FA = WN / 32;             // 32-row MFMA tiles along the output columns
     static constexpr int FB = BM / 32;             // 32-column MFMA tiles along the tokens
     static constexpr int X_CHUNKS = BM * 8 / kMmThreads;
-    static constexpr int W_CHUNKS = BN * 8 / kMmThreads;
     static constexpr int X_BYTES = BM * kRowBytes;
-    static constexpr int W_BYTES = BN * kRowBytes;
-    static constexpr int STAGE = X_BYTES + W_BYTES;
     static constexpr int C_STRIDE = (BN + 8) * 2;  // bytes; the pad staggers rows over the banks
     static constexpr int C_BYTES = BM * C_STRIDE;
-    static constexpr int LDS_BYTES = 2 * STAGE > C_BYTES ? 2 * STAGE : C_BYTES;
+    static constexpr int LDS_BYTES = kRing * X_BYTES > C_BYTES ? kRing * X_BYTES : C_BYTES;
     static_assert(BM % 32 == 0 && BN % 128 == 0, "tile must split into 32x32 MFMA tiles over four waves");
 };
 
 template <int BM, int BN>
 __global__ __launch_bounds__(kMmThreads) void mm_kernel(int T, int NC, int KD, int tiles_m, int tiles_n,
                                                         const uint16_t *__restrict__ A,
-                                                        const uint16_t *__restrict__ Bt,
+                                                        const uint16_t *__restrict__ Wf,
                                                         uint16_t *__restrict__ C)
 {
     using Tl = MmTile<BM, BN>;
@@ -107,8 +121,10 @@ __global__ __launch_bounds__(kMmThreads) void mm_kernel(int T, int NC, int KD, i
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int KT = KD / kBK;  // even: feature counts are multiples of 128
 
-    // global -> register -> LDS staging: thread handles chunk (row = idx / 8, chunk = idx % 8)
+    // token operand, global -> registers -> LDS: thread handles chunk (row = idx / 8, chunk = idx % 8)
     const uint16_t *x_src[Tl::X_CHUNKS];
     int x_dst[Tl::X_CHUNKS];
 #pragma unroll
@@ -120,14 +136,18 @@ __global__ __launch_bounds__(kMmThreads) void mm_kernel(int T, int NC, int KD, i
         x_src[n] = A + size_t(t) * KD + ch * 8;
         x_dst[n] = row * kRowBytes + swizzle(row, ch) * 16;
     }
-    const uint16_t *w_src[Tl::W_CHUNKS];
-    int w_dst[Tl::W_CHUNKS];
+    // weight fragments of this wave: block row (tn*BN + wave*WN)/32 + a, 1 KB per k-step, 16 bytes per lane
+    const uint16_t *w_src[Tl::FA];
 #pragma unroll
-    for (int n = 0; n < Tl::W_CHUNKS; ++n) {
-        const int idx = tid + kMmThreads * n;
-        const int row = idx >> 3, ch = idx & 7;
-        w_src[n] = Bt + size_t(tn * BN + row) * KD + ch * 8;
-        w_dst[n] = Tl::X_BYTES + row * kRowBytes + swizzle(row, ch) * 16;
+    for (int a = 0; a < Tl::FA; ++a)
+        w_src[a] = Wf + (size_t((tn * BN + wave * Tl::WN) / 32 + a) * (KD / 16) * 64 + lane) * 8;
+    // token fragments of this lane
+    int b_off[Tl::FB], b_sw[Tl::FB];
+#pragma unroll
+    for (int b = 0; b < Tl::FB; ++b) {
+        const int row = b * 32 + l32;
+        b_off[b] = row * kRowBytes;
+        b_sw[b] = (row >> 1) & 7;
     }
 
     f32x16 acc[Tl::FA][Tl::FB];
@@ -138,69 +158,85 @@ __global__ __launch_bounds__(kMmThreads) void mm_kernel(int T, int NC, int KD, i
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-    // fragment rows of this lane
-    const int l32 = lane & 31, half = lane >> 5;
-    int a_off[Tl::FA], a_sw[Tl::FA], b_off[Tl::FB], b_sw[Tl::FB];
-#pragma unroll
-    for (int a = 0; a < Tl::FA; ++a) {
-        const int row = wave * Tl::WN + a * 32 + l32;
-        a_off[a] = Tl::X_BYTES + row * kRowBytes;
-        a_sw[a] = (row >> 1) & 7;
-    }
-#pragma unroll
-    for (int b = 0; b < Tl::FB; ++b) {
-        const int row = b * 32 + l32;
-        b_off[b] = row * kRowBytes;
-        b_sw[b] = (row >> 1) & 7;
-    }
+    u32x4 xg0[Tl::X_CHUNKS], xg1[Tl::X_CHUNKS];       // token slices in flight from global memory
+    bf16x8 wf0[4][Tl::FA], wf1[4][Tl::FA];             // weight fragments of the current / next k-slice
+    bf16x8 xf0[Tl::FB], xf1[Tl::FB];                   // token fragments of the current / next k-step
 
-    // Software pipeline: the global loads of k-slice kt+1 are in flight while slice kt is multiplied
-    // out of LDS; they are parked in LDS (other buffer) afterwards.  One barrier per slice.
-    const int KT = KD / kBK;
-    u32x4 x_reg[Tl::X_CHUNKS], w_reg[Tl::W_CHUNKS];
-#define DD_LOAD_STAGE(kt_)                                                                              \
-    _Pragma("unroll") for (int n = 0; n < Tl::X_CHUNKS; ++n)                                            \
-        x_reg[n] = *reinterpret_cast<const u32x4 *>(x_src[n] + (kt_) * kBK);                            \
-    _Pragma("unroll") for (int n = 0; n < Tl::W_CHUNKS; ++n)                                            \
-        w_reg[n] = *reinterpret_cast<const u32x4 *>(w_src[n] + (kt_) * kBK);
-#define DD_STORE_STAGE(s_)                                                                              \
-    _Pragma("unroll") for (int n = 0; n < Tl::X_CHUNKS; ++n)                                            \
-        *reinterpret_cast<u32x4 *>(smem + (s_) * Tl::STAGE + x_dst[n]) = x_reg[n];                      \
-    _Pragma("unroll") for (int n = 0; n < Tl::W_CHUNKS; ++n)                                            \
-        *reinterpret_cast<u32x4 *>(smem + (s_) * Tl::STAGE + w_dst[n]) = w_reg[n];
-#define DD_COMPUTE_STAGE(s_)                                                                            \
-    _Pragma("unroll") for (int ks = 0; ks < kBK / 16; ++ks) {                                           \
-        const unsigned char *base = smem + (s_) * Tl::STAGE;                                            \
-        const int ch = ks * 2 + half;                                                                   \
-        bf16x8 fa[Tl::FA], fb[Tl::FB];                                                                  \
-        _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a)                                              \
-            fa[a] = *reinterpret_cast<const bf16x8 *>(base + a_off[a] + ((ch ^ a_sw[a]) << 4));         \
+#define DD_LOAD_X(xg_, kt_)                                                                             \
+    {                                                                                                   \
+        const int kk = ((kt_) < KT ? (kt_) : KT - 1) * kBK;                                             \
+        _Pragma("unroll") for (int n = 0; n < Tl::X_CHUNKS; ++n)                                        \
+            xg_[n] = *reinterpret_cast<const u32x4 *>(x_src[n] + kk);                                   \
+    }
+#define DD_STORE_X(xg_, kt_)                                                                            \
+    {                                                                                                   \
+        unsigned char *dstb = smem + ((kt_) % kRing) * Tl::X_BYTES;                                     \
+        _Pragma("unroll") for (int n = 0; n < Tl::X_CHUNKS; ++n)                                        \
+            *reinterpret_cast<u32x4 *>(dstb + x_dst[n]) = xg_[n];                                       \
+    }
+#define DD_LOAD_W(wf_, kt_)                                                                             \
+    {                                                                                                   \
+        const size_t kk = size_t((kt_) < KT ? (kt_) : KT - 1) * 4 * 512;                                \
+        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                                \
+            _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a)                                          \
+                wf_[ks][a] = *reinterpret_cast<const bf16x8 *>(w_src[a] + kk + ks * 512);               \
+    }
+#define DD_LOAD_XF(xf_, kt_, ks_)                                                                       \
+    {                                                                                                   \
+        const unsigned char *srcb = smem + ((kt_) % kRing) * Tl::X_BYTES;                               \
+        const int ch = (ks_) * 2 + half;                                                                \
         _Pragma("unroll") for (int b = 0; b < Tl::FB; ++b)                                              \
-            fb[b] = *reinterpret_cast<const bf16x8 *>(base + b_off[b] + ((ch ^ b_sw[b]) << 4));         \
-        _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a)                                              \
-            _Pragma("unroll") for (int b = 0; b < Tl::FB; ++b)                                          \
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);  \
+            xf_[b] = *reinterpret_cast<const bf16x8 *>(srcb + b_off[b] + ((ch ^ b_sw[b]) << 4));        \
     }
+#define DD_MFMA(wf_, ks_, xf_)                                                                          \
+    _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a)                                                  \
+        _Pragma("unroll") for (int b = 0; b < Tl::FB; ++b)                                              \
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf_[ks_][a], xf_[b], acc[a][b], 0, 0, 0);
+    // One k-slice: four k-steps; the token fragments of the next k-step are fetched from LDS while
+    // the current one is multiplied; then the slice two ahead is parked in LDS and a new one requested.
+#define DD_SLICE(kt_, wf_cur_, wf_next_, xg_)                                                           \
+    DD_LOAD_W(wf_next_, (kt_) + 1)                                                                      \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_LOAD_XF(xf1, kt_, 1)                                                                             \
+    DD_MFMA(wf_cur_, 0, xf0)                                                                            \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_LOAD_XF(xf0, kt_, 2)                                                                             \
+    DD_MFMA(wf_cur_, 1, xf1)                                                                            \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_LOAD_XF(xf1, kt_, 3)                                                                             \
+    DD_MFMA(wf_cur_, 2, xf0)                                                                            \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_LOAD_XF(xf0, (kt_) + 1, 0)                                                                       \
+    DD_MFMA(wf_cur_, 3, xf1)                                                                            \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_STORE_X(xg_, (kt_) + 2)                                                                          \
+    DD_LOAD_X(xg_, (kt_) + 4)                                                                           \
+    __syncthreads();
 
-    DD_LOAD_STAGE(0)
-    DD_STORE_STAGE(0)
+    // prologue: slices 0 and 1 in LDS, slices 2 and 3 in flight, weight fragments of slice 0 loaded
+    DD_LOAD_X(xg0, 0)
+    DD_LOAD_X(xg1, 1)
+    DD_LOAD_W(wf0, 0)
+    DD_STORE_X(xg0, 0)
+    DD_STORE_X(xg1, 1)
+    DD_LOAD_X(xg0, 2)
+    DD_LOAD_X(xg1, 3)
     __syncthreads();
-    for (int kt = 0; kt + 1 < KT; ++kt) {
-        DD_LOAD_STAGE(kt + 1)
-        __builtin_amdgcn_sched_barrier(0);  // keep the loads ahead of the multiply, not behind it
-        DD_COMPUTE_STAGE(kt & 1)
-        __builtin_amdgcn_sched_barrier(0);
-        DD_STORE_STAGE((kt + 1) & 1)
-        __syncthreads();
+    DD_LOAD_XF(xf0, 0, 0)
+    for (int kt = 0; kt < KT; kt += 2) {
+        DD_SLICE(kt, wf0, wf1, xg0)
+        DD_SLICE(kt + 1, wf1, wf0, xg1)
     }
-    DD_COMPUTE_STAGE((KT - 1) & 1)
-    __syncthreads();
-#undef DD_LOAD_STAGE
-#undef DD_STORE_STAGE
-#undef DD_COMPUTE_STAGE
+#undef DD_LOAD_X
+#undef DD_STORE_X
+#undef DD_LOAD_W
+#undef DD_LOAD_XF
+#undef DD_MFMA
+#undef DD_SLICE
 
     // Epilogue.  Accumulator i of lane l is output column 8*(i/4) + 4*(l/32) + i%4 of token l%32
     // inside its 32x32 tile: four consecutive columns per group, written as one 8-byte LDS store.
+    // (The last barrier of the loop has retired every read of the ring.)
 #pragma unroll
     for (int a = 0; a < Tl::FA; ++a)
 #pragma unroll
@@ -219,8 +255,8 @@ __global__ __launch_bounds__(kMmThreads) void mm_kernel(int T, int NC, int KD, i
         const int row = idx / ROW_CHUNKS, ch = idx % ROW_CHUNKS;
         const int t = tm * BM + row;
         if (t < T)
-            *reinterpret_cast<uint4 *>(C + size_t(t) * NC + tn * BN + ch * 8) =
-                *reinterpret_cast<const uint4 *>(smem + row * Tl::C_STRIDE + ch * 16);
+            *reinterpret_cast<u32x4 *>(C + size_t(t) * NC + tn * BN + ch * 8) =
+                *reinterpret_cast<const u32x4 *>(smem + row * Tl::C_STRIDE + ch * 16);
     }
 }
 
@@ -235,7 +271,7 @@ bool product_matrix_supported(int64_t T, int D, int L, bool bf16)
 size_t product_matrix_ws_bytes(int D, int L) { return size_t(D) * size_t(L) * 2; }
 
 template <int BM, int BN>
-static hipError_t launch_mm(int T, int NC, int KD, const uint16_t *A, const uint16_t *Bt, uint16_t *C,
+static hipError_t launch_mm(int T, int NC, int KD, const uint16_t *A, const uint16_t *Wf, uint16_t *C,
                             hipStream_t stream)
 {
     using Tl = MmTile<BM, BN>;
@@ -249,7 +285,7 @@ static hipError_t launch_mm(int T, int NC, int KD, const uint16_t *A, const uint
     const int tiles_m = (T + BM - 1) / BM, tiles_n = NC / BN;
     const int per_xcd = (tiles_m * tiles_n + kXcds - 1) / kXcds;
     hipLaunchKernelGGL((mm_kernel<BM, BN>), dim3(per_xcd * kXcds), dim3(kMmThreads), Tl::LDS_BYTES, stream, T, NC, KD,
-                       tiles_m, tiles_n, A, Bt, C);
+                       tiles_m, tiles_n, A, Wf, C);
     return hipGetLastError();
 }
 
@@ -275,9 +311,9 @@ hipError_t launch_product_matrix(const ProductArgs &a, hipStream_t stream)
     // masked gather: dst has D columns, contraction over the L columns of src  -> operand rows are long-side
     const int NC = a.masked ? a.D : a.L;
     const int KD = a.masked ? a.L : a.D;
-    uint16_t *Bt = static_cast<uint16_t *>(a.ws);
+    uint16_t *Wf = static_cast<uint16_t *>(a.ws);
     hipLaunchKernelGGL(materialize_kernel, dim3(NC), dim3(256), size_t(KD) * sizeof(float), stream, a.D, a.L, a.K,
-                       a.masked ? 1 : 0, a.offsets, static_cast<const uint16_t *>(a.values), Bt);
+                       a.masked ? 1 : 0, a.offsets, static_cast<const uint16_t *>(a.values), Wf);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const uint16_t *A = static_cast<const uint16_t *>(a.src);
@@ -285,14 +321,14 @@ hipError_t launch_product_matrix(const ProductArgs &a, hipStream_t stream)
     const int T = int(a.T);
     if (NC % 256 == 0) {
         switch (pick_tile(a.T, NC)) {
-        case 192: return launch_mm<192, 256>(T, NC, KD, A, Bt, C, stream);
-        case 160: return launch_mm<160, 256>(T, NC, KD, A, Bt, C, stream);
-        case 128: return launch_mm<128, 256>(T, NC, KD, A, Bt, C, stream);
-        case 96: return launch_mm<96, 256>(T, NC, KD, A, Bt, C, stream);
-        default: return launch_mm<64, 256>(T, NC, KD, A, Bt, C, stream);
+        case 192: return launch_mm<192, 256>(T, NC, KD, A, Wf, C, stream);
+        case 160: return launch_mm<160, 256>(T, NC, KD, A, Wf, C, stream);
+        case 128: return launch_mm<128, 256>(T, NC, KD, A, Wf, C, stream);
+        case 96: return launch_mm<96, 256>(T, NC, KD, A, Wf, C, stream);
+        default: return launch_mm<64, 256>(T, NC, KD, A, Wf, C, stream);
         }
     }
-    return launch_mm<128, 128>(T, NC, KD, A, Bt, C, stream);
+    return launch_mm<128, 128>(T, NC, KD, A, Wf, C, stream);
 }
 
 }  // namespace dd
