@@ -12,8 +12,9 @@
 //   operands: both are stored token-major, the MFMA wants the contraction index contiguous per lane, so
 //             token slices go to LDS as they are and come back through ds_read_b64_tr_b16, which hands
 //             each lane four consecutive tokens of one feature.
-//   select:   a table offset -> first diagonal with that offset (built by a one-workgroup kernel) picks
-//             the entries of each accumulator tile; repeated offsets read the same partial sums.
+//   select:   a table offset -> first diagonal with that offset (built in LDS by every workgroup while its
+//             first token slices are in flight) picks the entries of each accumulator tile; repeated
+//             offsets read the same partial sums.
 #include "dd_common.h"
 #include "dd_launch.h"
 
@@ -25,30 +26,30 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWgT = 256;           // threads
-constexpr int kTP = 128;            // tile extent along the short side (rows of the MFMA)
-constexpr int kTQ = 256;            // tile extent along the long side (columns of the MFMA)
 constexpr int kTS = 64;             // tokens per LDS stage
 constexpr int kPad = 64;            // bytes added to every LDS row: rows of one transposing read fall on distinct banks
-constexpr int kARow = kTP * 2 + kPad;
-constexpr int kBRow = kTQ * 2 + kPad;
-constexpr int kABytes = kTS * kARow;
-constexpr int kBBytes = kTS * kBRow;
-constexpr int kStageBytes = kABytes + kBBytes;
-constexpr int kAChunks = kTS * (kTP / 8) / kWgT;   // 16-byte pieces per thread per stage
-constexpr int kBChunks = kTS * (kTQ / 8) / kWgT;
 constexpr int kNoDiagonal = INT_MAX;
+constexpr int kWgXcds = 8;          // L2 caches (one per XCD); workgroups are dealt to them round-robin
+constexpr int kCusPerXcd = 32;
 
-// table[delta] = smallest k with canonical offset delta, or kNoDiagonal.  One workgroup.
-__global__ __launch_bounds__(1024) void offset_table_kernel(int D, int K, const int *__restrict__ offsets,
-                                                            int *__restrict__ table)
-{
-    for (int i = threadIdx.x; i < D; i += 1024) table[i] = kNoDiagonal;
-    __syncthreads();
-    for (int k = threadIdx.x; k < K; k += 1024) atomicMin(&table[canonical_offset(offsets[k], D)], k);
-}
+// Tile of G per workgroup: TP short-side x TQ long-side entries, four waves in a 2 x 2 arrangement.
+template <int TP, int TQ>
+struct WgTile {
+    static constexpr int FA = TP / 64;             // 32-row MFMA tiles per wave
+    static constexpr int FB = TQ / 64;             // 32-column MFMA tiles per wave
+    static constexpr int ARow = TP * 2 + kPad;
+    static constexpr int BRow = TQ * 2 + kPad;
+    static constexpr int ABytes = kTS * ARow;
+    static constexpr int BBytes = kTS * BRow;
+    static constexpr int StageBytes = ABytes + BBytes;
+    static constexpr int AChunks = kTS * (TP / 8) / kWgT;   // 16-byte pieces per thread per stage
+    static constexpr int BChunks = kTS * (TQ / 8) / kWgT;
+    static_assert(TP % 64 == 0 && TQ % 64 == 0, "wave tiles are made of 32x32 MFMA tiles");
+};
 
 __device__ __forceinline__ bf16x8 read_transposed(const unsigned char *p0, const unsigned char *p1)
 {
@@ -61,19 +62,32 @@ __device__ __forceinline__ bf16x8 read_transposed(const unsigned char *p0, const
 }
 
 // partial[split][k][p] for the representatives k of this tile's active offsets
+template <int TP, int TQ>
 __global__ __launch_bounds__(kWgT) void wgrad_mm_kernel(int T, int D, int L, int K, int tiles_p, int tiles_q,
-                                                        int tokens_per_split, const uint16_t *__restrict__ A,
+                                                        int splits, int slices,
+                                                        const uint16_t *__restrict__ A,
                                                         const uint16_t *__restrict__ B,
-                                                        const int *__restrict__ table, float *__restrict__ partial)
+                                                        const int *__restrict__ offsets, float *__restrict__ partial)
 {
     extern __shared__ __align__(16) unsigned char smem[];
+    using Tl = WgTile<TP, TQ>;
+    constexpr int kARow = Tl::ARow, kBRow = Tl::BRow, kABytes = Tl::ABytes, kStageBytes = Tl::StageBytes;
+    constexpr int kAChunks = Tl::AChunks, kBChunks = Tl::BChunks, kTP = TP, kTQ = TQ;
+    int *table = reinterpret_cast<int *>(smem + 2 * kStageBytes);  // [D]: offset -> first diagonal, or kNoDiagonal
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int tile = blockIdx.x % (tiles_p * tiles_q);
-    const int split = blockIdx.x / (tiles_p * tiles_q);
+    // Token chunks are dealt to the XCDs: every tile of one chunk runs on the same L2, so the chunk's
+    // slices of X and dY come from HBM once and from that L2 for every other tile.
+    const int tiles = tiles_p * tiles_q;
+    const int xcd = blockIdx.x % kWgXcds, local = blockIdx.x / kWgXcds;
+    const int split = (local / tiles) * kWgXcds + xcd;
+    if (split >= splits) return;
+    const int tile = local % tiles;
     const int p0 = (tile / tiles_q) * kTP, q0 = (tile % tiles_q) * kTQ;
-    const int t_begin = split * tokens_per_split;
-    const int t_end = min(t_begin + tokens_per_split, T);
-    const int n_slices = (tokens_per_split + kTS - 1) / kTS;  // same for every split; tokens past t_end read as zero
+    // chunk `split` owns the 64-token slices [split * slices / splits, (split + 1) * slices / splits)
+    const int slice_begin = int(int64_t(split) * slices / splits), slice_end = int(int64_t(split + 1) * slices / splits);
+    const int t_begin = slice_begin * kTS;
+    const int t_end = min(slice_end * kTS, T);
+    const int n_slices = (slice_end - slice_begin + 1) & ~1;  // the pipeline runs in pairs; tokens past t_end add zero
 
     // global -> register -> LDS staging.  A piece is 8 features of one token.
     int a_row[kAChunks], a_col[kAChunks], b_row[kBChunks], b_col[kBChunks];
@@ -89,18 +103,26 @@ __global__ __launch_bounds__(kWgT) void wgrad_mm_kernel(int T, int D, int L, int
         b_row[n] = idx / (kTQ / 8);
         b_col[n] = (idx % (kTQ / 8)) * 8;
     }
-    u32x4 ag0[kAChunks], bg0[kBChunks];
+    const uint16_t *a_base[kAChunks], *b_base[kBChunks];
+#pragma unroll
+    for (int n = 0; n < kAChunks; ++n) a_base[n] = A + p0 + a_col[n];
+#pragma unroll
+    for (int n = 0; n < kBChunks; ++n) b_base[n] = B + q0 + b_col[n];
+    u32x4 ag0[kAChunks], bg0[kBChunks], ag1[kAChunks], bg1[kBChunks];
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    // Rows past the end of the chunk must add nothing: their short-side piece is replaced by zeros (one
+    // zero factor is enough); the loads themselves stay in bounds by re-reading the last token.
 #define DD_WG_LOAD(ag_, bg_, s_)                                                                        \
     {                                                                                                   \
         const int tb = t_begin + (s_) * kTS;                                                            \
         _Pragma("unroll") for (int n = 0; n < kAChunks; ++n) {                                          \
             const int t = tb + a_row[n];                                                                \
-            ag_[n] = t < t_end ? *reinterpret_cast<const u32x4 *>(A + size_t(t) * L + p0 + a_col[n]) : zero4; \
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(a_base[n] + size_t(min(t, T - 1)) * L);    \
+            ag_[n] = t < t_end ? v : zero4;                                                             \
         }                                                                                               \
         _Pragma("unroll") for (int n = 0; n < kBChunks; ++n) {                                          \
-            const int t = tb + b_row[n];                                                                \
-            bg_[n] = t < t_end ? *reinterpret_cast<const u32x4 *>(B + size_t(t) * D + q0 + b_col[n]) : zero4; \
+            const int t = min(tb + b_row[n], T - 1);                                                    \
+            bg_[n] = *reinterpret_cast<const u32x4 *>(b_base[n] + size_t(t) * D);                       \
         }                                                                                               \
     }
 #define DD_WG_STORE(ag_, bg_, buf_)                                                                     \
@@ -118,83 +140,154 @@ __global__ __launch_bounds__(kWgT) void wgrad_mm_kernel(int T, int D, int L, int
     const int s16 = lane & 15, grp = lane >> 4;
     const int frag_row = (grp >> 1) * 8 + (s16 >> 2);
     const int frag_col = (grp & 1) * 16 + (s16 & 3) * 4;
-    const int wp = wave >> 1, wq = wave & 1;     // wave tile: rows wp*64.., columns wq*128..
-    const int a_frag = frag_row * kARow + (wp * 64 + frag_col) * 2;
-    const int b_frag = kABytes + frag_row * kBRow + (wq * 128 + frag_col) * 2;
+    const int wp = wave >> 1, wq = wave & 1;     // wave tile: rows wp*TP/2.., columns wq*TQ/2..
+    const int a_frag = frag_row * kARow + (wp * (TP / 2) + frag_col) * 2;
+    const int b_frag = kABytes + frag_row * kBRow + (wq * (TQ / 2) + frag_col) * 2;
 
-    f32x16 acc[2][4];
+    f32x16 acc[Tl::FA][Tl::FB];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < Tl::FA; ++a)
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
+        for (int b = 0; b < Tl::FB; ++b)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-#define DD_WG_COMPUTE(buf_)                                                                             \
-    _Pragma("unroll") for (int ks = 0; ks < kTS / 16; ++ks) {                                           \
+#define DD_WG_FRAGS(fa_, fb_, buf_, ks_)                                                                 \
+    {                                                                                                   \
         const unsigned char *base = smem + (buf_) * kStageBytes;                                        \
-        bf16x8 fa[2], fb[4];                                                                            \
-        _Pragma("unroll") for (int a = 0; a < 2; ++a) {                                                 \
-            const unsigned char *p = base + a_frag + ks * 16 * kARow + a * 64;                          \
-            fa[a] = read_transposed(p, p + 4 * kARow);                                                  \
+        _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a) {                                            \
+            const unsigned char *p = base + a_frag + (ks_) * 16 * kARow + a * 64;                       \
+            fa_[a] = read_transposed(p, p + 4 * kARow);                                                 \
         }                                                                                               \
-        _Pragma("unroll") for (int b = 0; b < 4; ++b) {                                                 \
-            const unsigned char *p = base + b_frag + ks * 16 * kBRow + b * 64;                          \
-            fb[b] = read_transposed(p, p + 4 * kBRow);                                                  \
+        _Pragma("unroll") for (int b = 0; b < Tl::FB; ++b) {                                            \
+            const unsigned char *p = base + b_frag + (ks_) * 16 * kBRow + b * 64;                       \
+            fb_[b] = read_transposed(p, p + 4 * kBRow);                                                 \
         }                                                                                               \
-        _Pragma("unroll") for (int a = 0; a < 2; ++a)                                                   \
-            _Pragma("unroll") for (int b = 0; b < 4; ++b)                                               \
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);  \
     }
+#define DD_WG_MFMA(fa_, fb_)                                                                            \
+    _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a)                                                  \
+        _Pragma("unroll") for (int b = 0; b < Tl::FB; ++b)                                              \
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa_[a], fb_[b], acc[a][b], 0, 0, 0);
+    // four k-steps of one slice; the fragments of the next k-step are fetched while the current one multiplies
+#define DD_WG_COMPUTE(buf_)                                                                             \
+    DD_WG_FRAGS(fa0, fb0, buf_, 0)                                                                      \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_WG_FRAGS(fa1, fb1, buf_, 1)                                                                      \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_WG_MFMA(fa0, fb0)                                                                                \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_WG_FRAGS(fa0, fb0, buf_, 2)                                                                      \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_WG_MFMA(fa1, fb1)                                                                                \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_WG_FRAGS(fa1, fb1, buf_, 3)                                                                      \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_WG_MFMA(fa0, fb0)                                                                                \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_WG_MFMA(fa1, fb1)
+    bf16x8 fa0[Tl::FA], fb0[Tl::FB], fa1[Tl::FA], fb1[Tl::FB];
 
-    // one slice in flight in registers while the previous one is multiplied out of LDS; two LDS buffers,
-    // one barrier per slice
+    // Two slices in flight in registers, two LDS buffers, one barrier per slice; the number of slices is
+    // even.  The offset table is filled in LDS while the first slices travel.
     DD_WG_LOAD(ag0, bg0, 0)
+    DD_WG_LOAD(ag1, bg1, 1)
+    for (int i = tid; i < D; i += kWgT) table[i] = kNoDiagonal;
+    __syncthreads();
+    for (int k = tid; k < K; k += kWgT) atomicMin(&table[canonical_offset(offsets[k], D)], k);
     DD_WG_STORE(ag0, bg0, 0)
     __syncthreads();
-    for (int s = 0; s < n_slices; ++s) {
-        DD_WG_LOAD(ag0, bg0, s + 1)
+    for (int s = 0; s < n_slices; s += 2) {
+        DD_WG_LOAD(ag0, bg0, s + 2)
         __builtin_amdgcn_sched_barrier(0);
-        DD_WG_COMPUTE(s & 1)
+        DD_WG_COMPUTE(0)
         __builtin_amdgcn_sched_barrier(0);
-        DD_WG_STORE(ag0, bg0, (s + 1) & 1)
+        DD_WG_STORE(ag1, bg1, 1)
+        __syncthreads();
+        DD_WG_LOAD(ag1, bg1, s + 3)
+        __builtin_amdgcn_sched_barrier(0);
+        DD_WG_COMPUTE(1)
+        __builtin_amdgcn_sched_barrier(0);
+        DD_WG_STORE(ag0, bg0, 0)
         __syncthreads();
     }
 #undef DD_WG_LOAD
 #undef DD_WG_STORE
 #undef DD_WG_COMPUTE
+#undef DD_WG_FRAGS
+#undef DD_WG_MFMA
 
-    // Keep the entries on active diagonals.  Accumulator i of lane l: row 8*(i/4) + 4*(l/32) + i%4,
-    // column l%32 of its 32x32 tile.
+    // Keep the entries on active diagonals, one 32x32 accumulator tile at a time.  Accumulator i of lane l
+    // is row 8*(i/4) + 4*(l/32) + i%4, column l%32 of the tile.  The tile is laid out column-major in a
+    // small LDS buffer of the wave's own; the 63 offsets that cross it are looked up at once (one per
+    // lane); every active one is then read back along the diagonal, lane = row, so that the partial sums
+    // of one diagonal leave as one contiguous run.  (The loop's last barrier retired all stage reads.)
+    constexpr int kTileStride = 36;  // floats per tile column: 16-byte aligned rows of four, odd diagonal stride
+    float *tilebuf = reinterpret_cast<float *>(smem) + wave * (32 * kTileStride);
     float *out = partial + size_t(split) * K * L;
     const int l32 = lane & 31, half = lane >> 5;
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < Tl::FA; ++a)
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int q = q0 + wq * 128 + b * 32 + l32;
+        for (int b = 0; b < Tl::FB; ++b) {
+            const int pb = p0 + wp * (TP / 2) + a * 32, qb = q0 + wq * (TQ / 2) + b * 32;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int p = p0 + wp * 64 + a * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-                int delta = q - p;
-                if (delta < 0) delta += D;
-                const int k = table[delta];
-                if (k != kNoDiagonal) out[size_t(k) * L + p] = acc[a][b][i];
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 v = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
+                *reinterpret_cast<f32x4 *>(tilebuf + l32 * kTileStride + 8 * g + 4 * half) = v;
             }
+            // lane j < 63 looks up the diagonal with (column - row) = j - 31 inside this tile
+            int delta = qb - pb + lane - 31;
+            delta = delta < 0 ? delta + D : (delta >= D ? delta - D : delta);
+            const int kj = lane < 63 ? table[delta] : kNoDiagonal;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            unsigned long long active = __ballot(kj != kNoDiagonal);
+            // four diagonals per round, two per half-wave, so that their LDS reads overlap
+            while (active) {
+                int j[4], kk[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    j[u] = active ? __builtin_ctzll(active) : 63;  // lane 63 never holds a diagonal
+                    active &= active - 1;                          // no-op once empty
+                    kk[u] = __builtin_amdgcn_readlane(kj, j[u]);
+                }
+                float v[2];
+                int kd[2];
+                bool ok[2];
+#pragma unroll
+                for (int uu = 0; uu < 2; ++uu) {
+                    const int jj = half ? j[2 * uu + 1] : j[2 * uu];
+                    kd[uu] = half ? kk[2 * uu + 1] : kk[2 * uu];
+                    const int col = l32 + jj - 31;  // column of this lane's row on that diagonal
+                    ok[uu] = kd[uu] != kNoDiagonal && col >= 0 && col < 32;
+                    v[uu] = ok[uu] ? tilebuf[col * kTileStride + l32] : 0.f;
+                }
+#pragma unroll
+                for (int uu = 0; uu < 2; ++uu)
+                    if (ok[uu]) out[unsigned(kd[uu]) * unsigned(L) + unsigned(pb + l32)] = v[uu];
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
         }
 }
 
 // dV[k][p] = sum over splits, in order, of partial[split][rep(k)][p], rep(k) = first diagonal with k's offset
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(int D, int L, int K, int splits,
                                                            const int *__restrict__ offsets,
-                                                           const int *__restrict__ table,
                                                            const float *__restrict__ partial,
                                                            float *__restrict__ dV)
 {
+    __shared__ int rep_s;
     const int k = blockIdx.y;
+    if (threadIdx.x == 0) rep_s = k;
+    __syncthreads();
+    const int mine = canonical_offset(offsets[k], D);
+    for (int j = threadIdx.x; j < k; j += 256)
+        if (canonical_offset(offsets[j], D) == mine) atomicMin(&rep_s, j);
+    __syncthreads();
+    const int rep = rep_s;
     const int p = blockIdx.x * 256 + threadIdx.x;
     if (p >= L) return;
-    const int rep = table[canonical_offset(offsets[k], D)];
     float acc = 0.f;
     for (int s = 0; s < splits; ++s) acc += partial[(size_t(s) * K + rep) * L + p];
     dV[size_t(k) * L + p] = acc;
@@ -203,62 +296,74 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(int D, int L, int K, 
 // ---- host side ----
 
 struct WgradPlan {
-    int tiles_p, tiles_q, splits, tokens_per_split;
+    int tp, tq;            // tile
+    int tiles_p, tiles_q;
+    int splits;            // token chunks (a multiple of the XCD count unless T is tiny)
+    int slices;            // T in units of 64 tokens
+    int grid;
 };
 
 static WgradPlan plan_wgrad(int64_t T, int D, int L)
 {
     WgradPlan pl;
-    pl.tiles_p = L / kTP;
-    pl.tiles_q = D / kTQ;
+    // 192 x 192 tiles keep the four waves square (96 x 96) and divide the ViT-Base widths; otherwise 128 x 256
+    if (L % 192 == 0 && D % 192 == 0) { pl.tp = 192; pl.tq = 192; } else { pl.tp = 128; pl.tq = 256; }
+    pl.tiles_p = L / pl.tp;
+    pl.tiles_q = D / pl.tq;
     const int tiles = pl.tiles_p * pl.tiles_q;
-    // as many token chunks as fit the 256 CUs in one round, each a whole number of 64-token slices
-    int splits = 256 / tiles;
+    // chunks per XCD: as many as fill its 32 CUs in one round
+    int per_xcd = kCusPerXcd / tiles;
+    if (per_xcd < 1) per_xcd = 1;
+    int64_t splits = int64_t(per_xcd) * kWgXcds;
     const int64_t slices = (T + kTS - 1) / kTS;
-    if (splits > slices) splits = int(slices);
-    if (splits < 1) splits = 1;
-    const int64_t per = ((slices + splits - 1) / splits) * kTS;
-    pl.tokens_per_split = int(per);
-    pl.splits = int((T + per - 1) / per);
+    if (splits > slices) splits = slices;
+    pl.slices = int(slices);
+    pl.splits = int(splits);
+    const int rounds = (pl.splits + kWgXcds - 1) / kWgXcds;
+    pl.grid = rounds * tiles * kWgXcds;
     return pl;
 }
 
 bool weight_grad_matrix_supported(int64_t T, int D, int L, bool bf16)
 {
-    return bf16 && T > 0 && T < (int64_t(1) << 31) && L % kTP == 0 && D % kTQ == 0 && D <= 8192;
+    if (!(bf16 && T > 0 && T < (int64_t(1) << 31) && D <= 8192)) return false;
+    return (L % 192 == 0 && D % 192 == 0) || (L % 128 == 0 && D % 256 == 0);
 }
-
-static size_t table_bytes(int D) { return (size_t(D) * sizeof(int) + 255) / 256 * 256; }
 
 size_t weight_grad_matrix_ws_bytes(int64_t T, int D, int L, int K)
 {
     const WgradPlan pl = plan_wgrad(T, D, L);
-    return table_bytes(D) + size_t(pl.splits) * K * L * sizeof(float);
+    return size_t(pl.splits) * K * L * sizeof(float);
+}
+
+template <int TP, int TQ>
+static hipError_t launch_wgrad_mm(const WeightGradArgs &a, const WgradPlan &pl, float *partial, hipStream_t stream)
+{
+    using Tl = WgTile<TP, TQ>;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_mm_kernel<TP, TQ>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           2 * Tl::StageBytes + 8192 * int(sizeof(int)));
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int lds_bytes = 2 * Tl::StageBytes + a.D * int(sizeof(int));
+    hipLaunchKernelGGL((wgrad_mm_kernel<TP, TQ>), dim3(pl.grid), dim3(kWgT), lds_bytes, stream, int(a.T), a.D, a.L,
+                       a.K, pl.tiles_p, pl.tiles_q, pl.splits, pl.slices,
+                       static_cast<const uint16_t *>(a.A), static_cast<const uint16_t *>(a.B), a.offsets, partial);
+    return hipGetLastError();
 }
 
 hipError_t launch_weight_grad_matrix(const WeightGradArgs &a, hipStream_t stream)
 {
     const WgradPlan pl = plan_wgrad(a.T, a.D, a.L);
-    int *table = static_cast<int *>(a.ws);
-    float *partial = reinterpret_cast<float *>(static_cast<unsigned char *>(a.ws) + table_bytes(a.D));
-    hipLaunchKernelGGL(offset_table_kernel, dim3(1), dim3(1024), 0, stream, a.D, a.K, a.offsets, table);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    static bool configured = false;
-    if (!configured) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_mm_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
-    const int grid = pl.tiles_p * pl.tiles_q * pl.splits;
-    hipLaunchKernelGGL(wgrad_mm_kernel, dim3(grid), dim3(kWgT), 2 * kStageBytes, stream, int(a.T), a.D, a.L, a.K,
-                       pl.tiles_p, pl.tiles_q, pl.tokens_per_split, static_cast<const uint16_t *>(a.A),
-                       static_cast<const uint16_t *>(a.B), table, partial);
-    e = hipGetLastError();
+    float *partial = static_cast<float *>(a.ws);
+    hipError_t e = pl.tp == 192 ? launch_wgrad_mm<192, 192>(a, pl, partial, stream)
+                                : launch_wgrad_mm<128, 256>(a, pl, partial, stream);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((a.L + 255) / 256, a.K), dim3(256), 0, stream, a.D, a.L, a.K,
-                       pl.splits, a.offsets, table, partial, a.dValues);
+                       pl.splits, a.offsets, partial, a.dValues);
     return hipGetLastError();
 }
 
