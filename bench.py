@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--algo", default="auto", choices=["auto", "vector", "matrix"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy a few times (a known-size reference for the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     return ap.parse_args()
 
 
@@ -136,6 +139,14 @@ def main():
 
     f_select(0)
     torch.cuda.synchronize()
+
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- the timed region of the contract: W warm-up steps, then exactly K steps ----
     for i in range(args.warmup):

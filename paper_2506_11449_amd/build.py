@@ -34,5 +34,19 @@ def build_library(verbose=False):
     return LIB_PATH
 
 
+CEILINGS_SRC = os.path.join(PKG_DIR, "ceilings", "ceilings.hip")
+CEILINGS_BIN = os.path.join(PKG_DIR, "ceilings", "ceilings")
+
+
+def build_ceilings():
+    """Compile the stand-alone ceilings microbenchmark (not part of the library)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17",
+                           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                           "-o", CEILINGS_BIN, CEILINGS_SRC])
+    return CEILINGS_BIN
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_ceilings())
