@@ -21,6 +21,10 @@
 #include "dd_common.h"
 #include "dd_launch.h"
 
+#ifndef DD_MM_WAVES
+#define DD_MM_WAVES 8
+#endif
+
 namespace dd {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -29,7 +33,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kMmThreads = 256;
 constexpr int kBK = 64;          // contraction extent of one LDS stage: 64 bf16 = 128 bytes per row
 constexpr int kRowBytes = kBK * 2;
 constexpr int kXcds = 8;
@@ -87,26 +90,29 @@ __global__ __launch_bounds__(256) void materialize_kernel(int D, int L, int K, i
 // ---------------------------------------------------------------------------------------------
 // Step 2: C [T x NC] = A [T x KD] . W,  W given fragment-major
 // ---------------------------------------------------------------------------------------------
-template <int BM, int BN>
+template <int BM, int BN, int NW>
 struct MmTile {
-    static constexpr int WN = BN / 4;              // output columns per wave
+    static constexpr int THREADS = 64 * NW;
+    static constexpr int WN = BN / NW;             // output columns per wave
     static constexpr int FA = WN / 32;             // 32-row MFMA tiles along the output columns
     static constexpr int FB = BM / 32;             // 32-column MFMA tiles along the tokens
-    static constexpr int X_CHUNKS = BM * 8 / kMmThreads;
+    static constexpr int X_CHUNKS = (BM * 8 + THREADS - 1) / THREADS;  // 16-byte pieces per thread per stage
     static constexpr int X_BYTES = BM * kRowBytes;
     static constexpr int C_STRIDE = (BN + 8) * 2;  // bytes; the pad staggers rows over the banks
     static constexpr int C_BYTES = BM * C_STRIDE;
     static constexpr int LDS_BYTES = kRing * X_BYTES > C_BYTES ? kRing * X_BYTES : C_BYTES;
-    static_assert(BM % 32 == 0 && BN % 128 == 0, "tile must split into 32x32 MFMA tiles over four waves");
+    static_assert(BM % 32 == 0 && BN % (32 * NW) == 0, "tile must split into 32x32 MFMA tiles over the waves");
+    static_assert((BM * 8) % 64 == 0, "a stage is filled by whole waves");
 };
 
-template <int BM, int BN>
-__global__ __launch_bounds__(kMmThreads) void mm_kernel(int T, int NC, int KD, int tiles_m, int tiles_n,
+template <int BM, int BN, int NW>
+__global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int tiles_m, int tiles_n,
                                                         const uint16_t *__restrict__ A,
                                                         const uint16_t *__restrict__ Wf,
                                                         uint16_t *__restrict__ C)
 {
-    using Tl = MmTile<BM, BN>;
+    using Tl = MmTile<BM, BN, NW>;
+    constexpr int kMmThreads = Tl::THREADS;
     extern __shared__ __align__(16) unsigned char smem[];
 
     // Workgroups are dealt round-robin to the eight XCDs, each with an L2 of its own.  Give every
@@ -129,7 +135,7 @@ __global__ __launch_bounds__(kMmThreads) void mm_kernel(int T, int NC, int KD, i
     int x_dst[Tl::X_CHUNKS];
 #pragma unroll
     for (int n = 0; n < Tl::X_CHUNKS; ++n) {
-        const int idx = tid + kMmThreads * n;
+        const int idx = min(tid + kMmThreads * n, BM * 8 - 1);  // a last partial round repeats the final piece
         const int row = idx >> 3, ch = idx & 7;
         int t = tm * BM + row;
         t = t < T ? t : T - 1;  // rows past the end re-read the last token; their results are not stored
@@ -270,24 +276,26 @@ bool product_matrix_supported(int64_t T, int D, int L, bool bf16)
 
 size_t product_matrix_ws_bytes(int D, int L) { return size_t(D) * size_t(L) * 2; }
 
-template <int BM, int BN>
+template <int BM, int BN, int NW>
 static hipError_t launch_mm(int T, int NC, int KD, const uint16_t *A, const uint16_t *Wf, uint16_t *C,
                             hipStream_t stream)
 {
-    using Tl = MmTile<BM, BN>;
+    using Tl = MmTile<BM, BN, NW>;
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&mm_kernel<BM, BN>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&mm_kernel<BM, BN, NW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, Tl::LDS_BYTES);
         if (e != hipSuccess) return e;
         configured = true;
     }
     const int tiles_m = (T + BM - 1) / BM, tiles_n = NC / BN;
     const int per_xcd = (tiles_m * tiles_n + kXcds - 1) / kXcds;
-    hipLaunchKernelGGL((mm_kernel<BM, BN>), dim3(per_xcd * kXcds), dim3(kMmThreads), Tl::LDS_BYTES, stream, T, NC, KD,
+    hipLaunchKernelGGL((mm_kernel<BM, BN, NW>), dim3(per_xcd * kXcds), dim3(Tl::THREADS), Tl::LDS_BYTES, stream, T, NC, KD,
                        tiles_m, tiles_n, A, Wf, C);
     return hipGetLastError();
 }
+
+constexpr int kMmWaves = DD_MM_WAVES;
 
 // Largest tile whose workgroup count fills the 256 CUs in the fewest, fullest rounds.
 static int pick_tile(int64_t T, int NC)
@@ -321,14 +329,14 @@ hipError_t launch_product_matrix(const ProductArgs &a, hipStream_t stream)
     const int T = int(a.T);
     if (NC % 256 == 0) {
         switch (pick_tile(a.T, NC)) {
-        case 192: return launch_mm<192, 256>(T, NC, KD, A, Wf, C, stream);
-        case 160: return launch_mm<160, 256>(T, NC, KD, A, Wf, C, stream);
-        case 128: return launch_mm<128, 256>(T, NC, KD, A, Wf, C, stream);
-        case 96: return launch_mm<96, 256>(T, NC, KD, A, Wf, C, stream);
-        default: return launch_mm<64, 256>(T, NC, KD, A, Wf, C, stream);
+        case 192: return launch_mm<192, 256, kMmWaves>(T, NC, KD, A, Wf, C, stream);
+        case 160: return launch_mm<160, 256, kMmWaves>(T, NC, KD, A, Wf, C, stream);
+        case 128: return launch_mm<128, 256, kMmWaves>(T, NC, KD, A, Wf, C, stream);
+        case 96: return launch_mm<96, 256, kMmWaves>(T, NC, KD, A, Wf, C, stream);
+        default: return launch_mm<64, 256, kMmWaves>(T, NC, KD, A, Wf, C, stream);
         }
     }
-    return launch_mm<128, 128>(T, NC, KD, A, Wf, C, stream);
+    return launch_mm<128, 128, 4>(T, NC, KD, A, Wf, C, stream);
 }
 
 }  // namespace dd

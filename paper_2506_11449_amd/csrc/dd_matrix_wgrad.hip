@@ -87,7 +87,8 @@ __global__ __launch_bounds__(kWgT) void wgrad_mm_kernel(int T, int D, int L, int
     const int slice_begin = int(int64_t(split) * slices / splits), slice_end = int(int64_t(split + 1) * slices / splits);
     const int t_begin = slice_begin * kTS;
     const int t_end = min(slice_end * kTS, T);
-    const int n_slices = (slice_end - slice_begin + 1) & ~1;  // the pipeline runs in pairs; tokens past t_end add zero
+    const int n_slices = slice_end - slice_begin;
+
 
     // global -> register -> LDS staging.  A piece is 8 features of one token.
     int a_row[kAChunks], a_col[kAChunks], b_row[kBChunks], b_col[kBChunks];
@@ -187,8 +188,8 @@ __global__ __launch_bounds__(kWgT) void wgrad_mm_kernel(int T, int D, int L, int
     DD_WG_MFMA(fa1, fb1)
     bf16x8 fa0[Tl::FA], fb0[Tl::FB], fa1[Tl::FA], fb1[Tl::FB];
 
-    // Two slices in flight in registers, two LDS buffers, one barrier per slice; the number of slices is
-    // even.  The offset table is filled in LDS while the first slices travel.
+    // Two slices in flight in registers, two LDS buffers, one barrier per slice; slices are taken in pairs,
+    // an odd last one on its own.  The offset table is filled in LDS while the first slices travel.
     DD_WG_LOAD(ag0, bg0, 0)
     DD_WG_LOAD(ag1, bg1, 1)
     for (int i = tid; i < D; i += kWgT) table[i] = kNoDiagonal;
@@ -196,7 +197,7 @@ __global__ __launch_bounds__(kWgT) void wgrad_mm_kernel(int T, int D, int L, int
     for (int k = tid; k < K; k += kWgT) atomicMin(&table[canonical_offset(offsets[k], D)], k);
     DD_WG_STORE(ag0, bg0, 0)
     __syncthreads();
-    for (int s = 0; s < n_slices; s += 2) {
+    for (int s = 0; s + 1 < n_slices; s += 2) {
         DD_WG_LOAD(ag0, bg0, s + 2)
         __builtin_amdgcn_sched_barrier(0);
         DD_WG_COMPUTE(0)
@@ -208,6 +209,10 @@ __global__ __launch_bounds__(kWgT) void wgrad_mm_kernel(int T, int D, int L, int
         DD_WG_COMPUTE(1)
         __builtin_amdgcn_sched_barrier(0);
         DD_WG_STORE(ag0, bg0, 0)
+        __syncthreads();
+    }
+    if (n_slices & 1) {  // uniform over the workgroup; the last slice sits in buffer 0
+        DD_WG_COMPUTE(0)
         __syncthreads();
     }
 #undef DD_WG_LOAD
