@@ -327,6 +327,9 @@ hipError_t launch_product_matrix(const ProductArgs &a, hipStream_t stream)
     const uint16_t *A = static_cast<const uint16_t *>(a.src);
     uint16_t *C = static_cast<uint16_t *>(a.dst);
     const int T = int(a.T);
+#ifdef DD_MM_FORCE
+    return launch_mm<DD_MM_FORCE>(T, NC, KD, A, Wf, C, stream);  // tuning builds only
+#endif
     if (NC % 256 == 0) {
         switch (pick_tile(a.T, NC)) {
         case 192: return launch_mm<192, 256, kMmWaves>(T, NC, KD, A, Wf, C, stream);
