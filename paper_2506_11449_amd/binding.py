@@ -58,7 +58,7 @@ def load_library():
 
 
 def _check(status):
-    if status != 0:
+    if status:
         raise DynaDiagError(status, load_library().dd_status_string(status).decode())
 
 
@@ -69,6 +69,21 @@ def make_layer(tokens, in_features, out_features, K, dtype, algo=DD_ALGO_AUTO):
     if isinstance(dtype, torch.dtype):
         dtype = _DTYPES[dtype]
     return dd_layer(int(tokens), int(in_features), int(out_features), int(K), int(dtype), int(algo))
+
+
+_plan_cache = {}
+
+
+def _plan(op, tokens, in_features, out_features, K, dtype, algo, batch=0):
+    """(layer struct, byref(layer), workspace bytes) for one entry point and shape, built once."""
+    key = (op, tokens, in_features, out_features, K, dtype, algo, batch)
+    hit = _plan_cache.get(key)
+    if hit is None:
+        layer = make_layer(tokens, in_features, out_features, K, dtype, algo)
+        ref = ctypes.byref(layer)
+        need = int(load_library().dd_workspace_bytes(int(op), ref, int(batch)))
+        hit = _plan_cache[key] = (layer, ref, need)
+    return hit
 
 
 def dd_workspace_bytes(op, layer, batch=0):
@@ -109,8 +124,7 @@ class Workspace:
 _default_ws = Workspace()
 
 
-def _ws_for(op, layer, device, ws, batch=0):
-    need = dd_workspace_bytes(op, layer, batch)
+def _ws_for(need, device, ws):
     buf, n = (ws or _default_ws).get(need, device)
     return _ptr(buf), n
 
@@ -120,16 +134,15 @@ def dd_fwd(X, offsets, values, out_features, Y=None, algo=DD_ALGO_AUTO, ws=None,
     T, M = X.shape
     N = int(out_features)
     K = offsets.shape[0]
-    layer = make_layer(T, M, N, K, X.dtype, algo)
+    _, ref, need = _plan(DD_OP_FWD, T, M, N, K, X.dtype, algo)
     _dev(X, X.dtype, (T, M), "X")
     _dev(offsets, torch.int32, (K,), "offsets")
     _dev(values, X.dtype, (K, min(M, N)), "values")
     if Y is None:
         Y = torch.empty((T, N), dtype=X.dtype, device=X.device)
     _dev(Y, X.dtype, (T, N), "Y")
-    wp, wn = _ws_for(DD_OP_FWD, layer, X.device, ws)
-    _check(load_library().dd_fwd(ctypes.byref(layer), _ptr(X), _ptr(offsets), _ptr(values), _ptr(Y), wp, wn,
-                                 _stream(stream)))
+    wp, wn = _ws_for(need, X.device, ws)
+    _check(_lib.dd_fwd(ref, _ptr(X), _ptr(offsets), _ptr(values), _ptr(Y), wp, wn, _stream(stream)))
     return Y
 
 
@@ -138,16 +151,15 @@ def dd_bwd_input(dY, offsets, values, in_features, dX=None, algo=DD_ALGO_AUTO, w
     T, N = dY.shape
     M = int(in_features)
     K = offsets.shape[0]
-    layer = make_layer(T, M, N, K, dY.dtype, algo)
+    _, ref, need = _plan(DD_OP_BWD_INPUT, T, M, N, K, dY.dtype, algo)
     _dev(dY, dY.dtype, (T, N), "dY")
     _dev(offsets, torch.int32, (K,), "offsets")
     _dev(values, dY.dtype, (K, min(M, N)), "values")
     if dX is None:
         dX = torch.empty((T, M), dtype=dY.dtype, device=dY.device)
     _dev(dX, dY.dtype, (T, M), "dX")
-    wp, wn = _ws_for(DD_OP_BWD_INPUT, layer, dY.device, ws)
-    _check(load_library().dd_bwd_input(ctypes.byref(layer), _ptr(dY), _ptr(offsets), _ptr(values), _ptr(dX), wp, wn,
-                                       _stream(stream)))
+    wp, wn = _ws_for(need, dY.device, ws)
+    _check(_lib.dd_bwd_input(ref, _ptr(dY), _ptr(offsets), _ptr(values), _ptr(dX), wp, wn, _stream(stream)))
     return dX
 
 
@@ -156,16 +168,15 @@ def dd_bwd_weight(X, dY, offsets, dValues=None, algo=DD_ALGO_AUTO, ws=None, stre
     T, M = X.shape
     N = dY.shape[1]
     K = offsets.shape[0]
-    layer = make_layer(T, M, N, K, X.dtype, algo)
+    _, ref, need = _plan(DD_OP_BWD_WEIGHT, T, M, N, K, X.dtype, algo)
     _dev(X, X.dtype, (T, M), "X")
     _dev(dY, X.dtype, (T, N), "dY")
     _dev(offsets, torch.int32, (K,), "offsets")
     if dValues is None:
         dValues = torch.empty((K, min(M, N)), dtype=torch.float32, device=X.device)
     _dev(dValues, torch.float32, (K, min(M, N)), "dValues")
-    wp, wn = _ws_for(DD_OP_BWD_WEIGHT, layer, X.device, ws)
-    _check(load_library().dd_bwd_weight(ctypes.byref(layer), _ptr(X), _ptr(dY), _ptr(offsets), _ptr(dValues), wp, wn,
-                                        _stream(stream)))
+    wp, wn = _ws_for(need, X.device, ws)
+    _check(_lib.dd_bwd_weight(ref, _ptr(X), _ptr(dY), _ptr(offsets), _ptr(dValues), wp, wn, _stream(stream)))
     return dValues
 
 
@@ -178,7 +189,7 @@ def dd_select_diagonals(scores, K, offsets_out=None, ws=None, stream=None):
     if offsets_out is None:
         offsets_out = torch.empty((B, K), dtype=torch.int32, device=scores.device)
     _dev(offsets_out, torch.int32, (B, K), "offsets_out")
-    layer = make_layer(0, D, D, K, DD_F32)
-    wp, wn = _ws_for(DD_OP_SELECT, layer, scores.device, ws, batch=B)
-    _check(load_library().dd_select_diagonals(B, D, int(K), _ptr(scores), _ptr(offsets_out), wp, wn, _stream(stream)))
+    _, _, need = _plan(DD_OP_SELECT, 0, D, D, int(K), DD_F32, DD_ALGO_AUTO, batch=B)
+    wp, wn = _ws_for(need, scores.device, ws)
+    _check(_lib.dd_select_diagonals(B, D, int(K), _ptr(scores), _ptr(offsets_out), wp, wn, _stream(stream)))
     return offsets_out

@@ -33,13 +33,19 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kBK = 64;          // contraction extent of one LDS stage: 64 bf16 = 128 bytes per row
+#ifndef DD_MM_BK
+#define DD_MM_BK 64
+#endif
+constexpr int kBK = DD_MM_BK;    // contraction extent of one LDS stage in bf16 elements (64 or 128)
+constexpr int kChunksPerRow = kBK / 8;  // 16-byte chunks per LDS row
+constexpr int kKSteps = kBK / 16;       // MFMA k-steps per stage
 constexpr int kRowBytes = kBK * 2;
 constexpr int kXcds = 8;
 constexpr int kRing = 3;         // LDS stages of the token operand
 
 // position of 16-byte chunk `chunk` (0..7) inside its 128-byte row
-__device__ __forceinline__ int swizzle(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
+__device__ __forceinline__ int swizzle_key(int row) { return kBK == 64 ? (row >> 1) & 7 : row & 15; }
+__device__ __forceinline__ int swizzle(int row, int chunk) { return chunk ^ swizzle_key(row); }
 
 // Fragment-major layout of the dense operand: element (output column j, contraction index i) of a
 // matrix with KD contraction indices.  Block (j / 32, i / 16) holds 64 lanes x 8 elements; lane
@@ -96,7 +102,7 @@ struct MmTile {
     static constexpr int WN = BN / NW;             // output columns per wave
     static constexpr int FA = WN / 32;             // 32-row MFMA tiles along the output columns
     static constexpr int FB = BM / 32;             // 32-column MFMA tiles along the tokens
-    static constexpr int X_CHUNKS = (BM * 8 + THREADS - 1) / THREADS;  // 16-byte pieces per thread per stage
+    static constexpr int X_CHUNKS = (BM * kChunksPerRow + THREADS - 1) / THREADS;  // 16-byte pieces per thread per stage
     static constexpr int X_BYTES = BM * kRowBytes;
     static constexpr int C_STRIDE = (BN + 8) * 2;  // bytes; the pad staggers rows over the banks
     static constexpr int C_BYTES = BM * C_STRIDE;
@@ -135,8 +141,8 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
     int x_dst[Tl::X_CHUNKS];
 #pragma unroll
     for (int n = 0; n < Tl::X_CHUNKS; ++n) {
-        const int idx = min(tid + kMmThreads * n, BM * 8 - 1);  // a last partial round repeats the final piece
-        const int row = idx >> 3, ch = idx & 7;
+        const int idx = min(tid + kMmThreads * n, BM * kChunksPerRow - 1);  // a last partial round repeats the final piece
+        const int row = idx / kChunksPerRow, ch = idx % kChunksPerRow;
         int t = tm * BM + row;
         t = t < T ? t : T - 1;  // rows past the end re-read the last token; their results are not stored
         x_src[n] = A + size_t(t) * KD + ch * 8;
@@ -153,7 +159,7 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
     for (int b = 0; b < Tl::FB; ++b) {
         const int row = b * 32 + l32;
         b_off[b] = row * kRowBytes;
-        b_sw[b] = (row >> 1) & 7;
+        b_sw[b] = swizzle_key(row);
     }
 
     f32x16 acc[Tl::FA][Tl::FB];
@@ -180,9 +186,10 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
         _Pragma("unroll") for (int n = 0; n < Tl::X_CHUNKS; ++n)                                        \
             *reinterpret_cast<u32x4 *>(dstb + x_dst[n]) = xg_[n];                                       \
     }
-#define DD_LOAD_W(wf_, kt_)                                                                             \
+#define DD_LOAD_W(wf_, g_) /* g_ counts groups of four k-steps (64 contraction indices) */            \
     {                                                                                                   \
-        const size_t kk = size_t((kt_) < KT ? (kt_) : KT - 1) * 4 * 512;                                \
+        const int gmax = KD / 64 - 1;                                                                   \
+        const size_t kk = size_t((g_) < gmax ? (g_) : gmax) * 4 * 512;                                  \
         _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                                \
             _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a)                                          \
                 wf_[ks][a] = *reinterpret_cast<const bf16x8 *>(w_src[a] + kk + ks * 512);               \
@@ -200,6 +207,7 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
             acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf_[ks_][a], xf_[b], acc[a][b], 0, 0, 0);
     // One k-slice: four k-steps; the token fragments of the next k-step are fetched from LDS while
     // the current one is multiplied; then the slice two ahead is parked in LDS and a new one requested.
+#if DD_MM_BK == 64
 #define DD_SLICE(kt_, wf_cur_, wf_next_, xg_)                                                           \
     DD_LOAD_W(wf_next_, (kt_) + 1)                                                                      \
     __builtin_amdgcn_sched_barrier(0);                                                                  \
@@ -218,11 +226,48 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
     DD_STORE_X(xg_, (kt_) + 2)                                                                          \
     DD_LOAD_X(xg_, (kt_) + 4)                                                                           \
     __syncthreads();
+#define DD_FIRST_W(wf_) DD_LOAD_W(wf_, 0)
+#else
+    /* a 128-wide stage: eight k-steps, the weight fragments come in two groups of four (wf0, then wf1) */
+#define DD_SLICE(kt_, wf_cur_, wf_next_, xg_)                                                           \
+    DD_LOAD_W(wf1, 2 * (kt_) + 1)                                                                       \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_LOAD_XF(xf1, kt_, 1)                                                                             \
+    DD_MFMA(wf0, 0, xf0)                                                                                \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_LOAD_XF(xf0, kt_, 2)                                                                             \
+    DD_MFMA(wf0, 1, xf1)                                                                                \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_LOAD_XF(xf1, kt_, 3)                                                                             \
+    DD_MFMA(wf0, 2, xf0)                                                                                \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_LOAD_XF(xf0, kt_, 4)                                                                             \
+    DD_MFMA(wf0, 3, xf1)                                                                                \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_LOAD_W(wf0, 2 * (kt_) + 2)                                                                       \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_LOAD_XF(xf1, kt_, 5)                                                                             \
+    DD_MFMA(wf1, 0, xf0)                                                                                \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_LOAD_XF(xf0, kt_, 6)                                                                             \
+    DD_MFMA(wf1, 1, xf1)                                                                                \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_LOAD_XF(xf1, kt_, 7)                                                                             \
+    DD_MFMA(wf1, 2, xf0)                                                                                \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_LOAD_XF(xf0, (kt_) + 1, 0)                                                                       \
+    DD_MFMA(wf1, 3, xf1)                                                                                \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_STORE_X(xg_, (kt_) + 2)                                                                          \
+    DD_LOAD_X(xg_, (kt_) + 4)                                                                           \
+    __syncthreads();
+#define DD_FIRST_W(wf_) DD_LOAD_W(wf_, 0)
+#endif
 
     // prologue: slices 0 and 1 in LDS, slices 2 and 3 in flight, weight fragments of slice 0 loaded
     DD_LOAD_X(xg0, 0)
     DD_LOAD_X(xg1, 1)
-    DD_LOAD_W(wf0, 0)
+    DD_FIRST_W(wf0)
     DD_STORE_X(xg0, 0)
     DD_STORE_X(xg1, 1)
     DD_LOAD_X(xg0, 2)
@@ -239,6 +284,7 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
 #undef DD_LOAD_XF
 #undef DD_MFMA
 #undef DD_SLICE
+#undef DD_FIRST_W
 
     // Epilogue.  Accumulator i of lane l is output column 8*(i/4) + 4*(l/32) + i%4 of token l%32
     // inside its 32x32 tile: four consecutive columns per group, written as one 8-byte LDS store.
