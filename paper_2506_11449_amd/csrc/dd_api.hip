@@ -107,7 +107,8 @@ size_t dd_workspace_bytes(int op, const dd_layer *layer, int32_t batch)
         return wants_matrix(layer, s) ? dd::product_matrix_ws_bytes(s.D, s.L) : 0;
     case DD_OP_BWD_WEIGHT:
         return wants_matrix_wgrad(layer, s) ? dd::weight_grad_matrix_ws_bytes(layer->tokens, s.D, s.L, layer->K)
-                                            : dd::weight_grad_vector_ws_bytes(layer->tokens, s.D, s.L, layer->K);
+                                            : dd::weight_grad_vector_ws_bytes(layer->tokens, s.D, s.L, layer->K,
+                                                                               layer->dtype == DD_BF16);
     default:
         return 0;
     }

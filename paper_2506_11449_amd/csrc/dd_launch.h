@@ -40,8 +40,13 @@ hipError_t launch_product_vector(const ProductArgs &a, hipStream_t stream);
 bool product_matrix_supported(int64_t T, int D, int L, bool bf16);
 size_t product_matrix_ws_bytes(int D, int L);
 hipError_t launch_product_matrix(const ProductArgs &a, hipStream_t stream);
-size_t weight_grad_vector_ws_bytes(int64_t T, int D, int L, int K);
+size_t weight_grad_vector_ws_bytes(int64_t T, int D, int L, int K, bool bf16);
 hipError_t launch_weight_grad_vector(const WeightGradArgs &a, hipStream_t stream);
+// bf16 dot-product kernel of the vector family (feature counts multiples of 8, long side <= 2304)
+bool weight_grad_dot2_supported(int64_t T, int D, int L, int K);
+size_t weight_grad_dot2_ws_bytes(int64_t T, int D, int L, int K);
+int weight_grad_dot2_chunks(int64_t T, int D, int L, int K);
+hipError_t launch_weight_grad_dot2_partials(const WeightGradArgs &a, hipStream_t stream);
 
 // matrix-core family (bf16 only, short side a multiple of 128, long side a multiple of 256)
 bool weight_grad_matrix_supported(int64_t T, int D, int L, bool bf16);

@@ -242,10 +242,12 @@ static int weight_grad_splits(int64_t T)
     return int(s);
 }
 
-size_t weight_grad_vector_ws_bytes(int64_t T, int D, int L, int K)
+size_t weight_grad_vector_ws_bytes(int64_t T, int D, int L, int K, bool bf16)
 {
-    (void)D;
-    return size_t(weight_grad_splits(T)) * size_t(K) * size_t(L) * sizeof(float);
+    // whichever kernel runs (the choice also depends on pointer alignment, unknown here) must fit
+    const size_t plain = size_t(weight_grad_splits(T)) * size_t(K) * size_t(L) * sizeof(float);
+    const size_t dot2 = bf16 && weight_grad_dot2_supported(T, D, L, K) ? weight_grad_dot2_ws_bytes(T, D, L, K) : 0;
+    return plain > dot2 ? plain : dot2;
 }
 
 // partial[s][k][p] = sum over the tokens of split s of A[t, p] * B[t, (p + o_k) mod D]
@@ -299,6 +301,15 @@ static hipError_t launch_weight_grad_t(const WeightGradArgs &a, hipStream_t stre
 
 hipError_t launch_weight_grad_vector(const WeightGradArgs &a, hipStream_t stream)
 {
+    const bool aligned = reinterpret_cast<uintptr_t>(a.A) % 16 == 0 && reinterpret_cast<uintptr_t>(a.B) % 16 == 0;
+    if (a.bf16 && aligned && weight_grad_dot2_supported(a.T, a.D, a.L, a.K)) {
+        hipError_t e = launch_weight_grad_dot2_partials(a, stream);
+        if (e != hipSuccess) return e;
+        const size_t n = size_t(a.K) * a.L;
+        hipLaunchKernelGGL(weight_grad_reduce_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, n,
+                           weight_grad_dot2_chunks(a.T, a.D, a.L, a.K), static_cast<const float *>(a.ws), a.dValues);
+        return hipGetLastError();
+    }
     return a.bf16 ? launch_weight_grad_t<BF16>(a, stream) : launch_weight_grad_t<F32>(a, stream);
 }
 
