@@ -30,6 +30,10 @@ SMALL = [
     (256, 128, 26, 161),
     (128, 384, 40, 415),
     (512, 512, 3, 700),
+    (128, 8192, 100, 70),
+    (8192, 128, 100, 70),
+    (2048, 2048, 20, 100),
+    (384, 1152, 60, 333),
     (33, 7, 4, 19),
     (7, 33, 4, 19),
     (1, 1, 1, 5),
@@ -208,6 +212,19 @@ def test_vitb_mlp_sampled(which, algo):
 def test_vitl_sampled(name, algo):
     layer = next(l for l in synth.WORKLOADS["vitl"] if l.name == name)
     _sampled_check(layer, 4096, ALGOS[algo], n_rows=24, n_entries=128)
+
+
+@pytest.mark.parametrize("algo", ["auto"])
+@pytest.mark.parametrize("which", [0, 4, 5])
+def test_vitb_stack_sampled(which, algo):
+    """One block of the ViT-Base-depth stack at 256 x 197 tokens: attention projection, fc1, fc2."""
+    _sampled_check(synth.WORKLOADS["vitb_stack"][which], 7000 + which, ALGOS[algo], n_rows=16, n_entries=96)
+
+
+def test_stack_selection_batched():
+    """The per-step re-selection of the stack: 48 score vectors of 768 and 24 of 3072 in two launches."""
+    for B, D, K in ((48, 768, 77), (24, 3072, 307)):
+        _select_check(synth.draw_scores(B, D, seed=B + D), K)
 
 
 # ---- selection: bit-exact ----
