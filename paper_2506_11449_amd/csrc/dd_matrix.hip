@@ -11,16 +11,19 @@
 //   a block of 32 output columns x 16 contraction indices is 1 KB, lane-major, so a wave fetches
 //   a fragment with one fully coalesced 16-byte-per-lane load and the operand never touches LDS.
 // Step 2 (mm_kernel): C [T x NC] = A [T x KD] . W with v_mfma_f32_32x32x16_bf16.  A workgroup of
-//   four waves owns a BM x BN tile of C; each wave owns BN/4 output columns (its weight fragments
+//   NW waves (eight by default: two per SIMD, so that one wave's waits hide behind the other's
+//   MFMAs) owns a BM x BN tile of C; each wave owns BN/NW output columns (its weight fragments
 //   are private, loaded global -> registers one k-slice ahead) and all BM tokens.  The token
-//   operand is shared by the four waves and goes through a three-deep LDS ring in 64-wide
-//   k-slices, XOR-swizzled in 16-byte chunks so that fragment reads are free of bank conflicts.
+//   operand is shared by all waves and goes through a three-deep LDS ring in 64-wide k-slices,
+//   XOR-swizzled in 16-byte chunks so that fragment reads are free of bank conflicts.
 //   The MFMA rows are output columns and the MFMA columns are tokens, which leaves every lane
 //   with four consecutive output columns of one token, so the tile is transposed back through
 //   LDS once and stored with full-width row segments.
 #include "dd_common.h"
 #include "dd_launch.h"
 
+// Tuning hooks for experiments (normal builds leave them alone): waves per workgroup, and
+// -DDD_MM_FORCE=BM,BN,NW to pin one tile shape.
 #ifndef DD_MM_WAVES
 #define DD_MM_WAVES 8
 #endif
@@ -33,18 +36,14 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-#ifndef DD_MM_BK
-#define DD_MM_BK 64
-#endif
-constexpr int kBK = DD_MM_BK;    // contraction extent of one LDS stage in bf16 elements (64 or 128)
+constexpr int kBK = 64;           // contraction extent of one LDS stage: 64 bf16 = 128 bytes per row
 constexpr int kChunksPerRow = kBK / 8;  // 16-byte chunks per LDS row
-constexpr int kKSteps = kBK / 16;       // MFMA k-steps per stage
 constexpr int kRowBytes = kBK * 2;
 constexpr int kXcds = 8;
 constexpr int kRing = 3;         // LDS stages of the token operand
 
 // position of 16-byte chunk `chunk` (0..7) inside its 128-byte row
-__device__ __forceinline__ int swizzle_key(int row) { return kBK == 64 ? (row >> 1) & 7 : row & 15; }
+__device__ __forceinline__ int swizzle_key(int row) { return (row >> 1) & 7; }
 __device__ __forceinline__ int swizzle(int row, int chunk) { return chunk ^ swizzle_key(row); }
 
 // Fragment-major layout of the dense operand: element (output column j, contraction index i) of a
@@ -207,7 +206,6 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
             acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf_[ks_][a], xf_[b], acc[a][b], 0, 0, 0);
     // One k-slice: four k-steps; the token fragments of the next k-step are fetched from LDS while
     // the current one is multiplied; then the slice two ahead is parked in LDS and a new one requested.
-#if DD_MM_BK == 64
 #define DD_SLICE(kt_, wf_cur_, wf_next_, xg_)                                                           \
     DD_LOAD_W(wf_next_, (kt_) + 1)                                                                      \
     __builtin_amdgcn_sched_barrier(0);                                                                  \
@@ -226,48 +224,11 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
     DD_STORE_X(xg_, (kt_) + 2)                                                                          \
     DD_LOAD_X(xg_, (kt_) + 4)                                                                           \
     __syncthreads();
-#define DD_FIRST_W(wf_) DD_LOAD_W(wf_, 0)
-#else
-    /* a 128-wide stage: eight k-steps, the weight fragments come in two groups of four (wf0, then wf1) */
-#define DD_SLICE(kt_, wf_cur_, wf_next_, xg_)                                                           \
-    DD_LOAD_W(wf1, 2 * (kt_) + 1)                                                                       \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_LOAD_XF(xf1, kt_, 1)                                                                             \
-    DD_MFMA(wf0, 0, xf0)                                                                                \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_LOAD_XF(xf0, kt_, 2)                                                                             \
-    DD_MFMA(wf0, 1, xf1)                                                                                \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_LOAD_XF(xf1, kt_, 3)                                                                             \
-    DD_MFMA(wf0, 2, xf0)                                                                                \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_LOAD_XF(xf0, kt_, 4)                                                                             \
-    DD_MFMA(wf0, 3, xf1)                                                                                \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_LOAD_W(wf0, 2 * (kt_) + 2)                                                                       \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_LOAD_XF(xf1, kt_, 5)                                                                             \
-    DD_MFMA(wf1, 0, xf0)                                                                                \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_LOAD_XF(xf0, kt_, 6)                                                                             \
-    DD_MFMA(wf1, 1, xf1)                                                                                \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_LOAD_XF(xf1, kt_, 7)                                                                             \
-    DD_MFMA(wf1, 2, xf0)                                                                                \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_LOAD_XF(xf0, (kt_) + 1, 0)                                                                       \
-    DD_MFMA(wf1, 3, xf1)                                                                                \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_STORE_X(xg_, (kt_) + 2)                                                                          \
-    DD_LOAD_X(xg_, (kt_) + 4)                                                                           \
-    __syncthreads();
-#define DD_FIRST_W(wf_) DD_LOAD_W(wf_, 0)
-#endif
 
     // prologue: slices 0 and 1 in LDS, slices 2 and 3 in flight, weight fragments of slice 0 loaded
     DD_LOAD_X(xg0, 0)
     DD_LOAD_X(xg1, 1)
-    DD_FIRST_W(wf0)
+    DD_LOAD_W(wf0, 0)
     DD_STORE_X(xg0, 0)
     DD_STORE_X(xg1, 1)
     DD_LOAD_X(xg0, 2)
@@ -284,7 +245,6 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
 #undef DD_LOAD_XF
 #undef DD_MFMA
 #undef DD_SLICE
-#undef DD_FIRST_W
 
     // Epilogue.  Accumulator i of lane l is output column 8*(i/4) + 4*(l/32) + i%4 of token l%32
     // inside its 32x32 tile: four consecutive columns per group, written as one 8-byte LDS store.
