@@ -11,6 +11,8 @@
  *   - backward dX = dY . W_K^T over the same diagonals                  (Sec. 3.3; Fig. 3 g)
  *   - backward dV: the gradient restricted to the K diagonals           (Fig. 3 h, i)
  *   - hard TopK choice of K of the D candidate diagonals                (Sec. 3.2, Eq. 4)
+ *   - soft TopK weights, their derivative, and the scaling of the
+ *     diagonals by them with its adjoint                                (Sec. 3.2, Eq. 4 and Eq. 5)
  *
  * Reading of the rectangular convention (the paper states it in two incompatible
  * ways; this is the one under which the K-from-sparsity footnote of Sec. 3.1, the
@@ -225,4 +227,84 @@ int ddo_select(int batch, int D, int K, const float *scores, int32_t *offsets_ou
     }
     free(buf);
     return 0;
+}
+
+/* ---- soft TopK weights and the scaling of the diagonals by them (Sec. 3.2, Eq. 4 and Eq. 5) ---- */
+
+/*
+ * Eq. 5: alpha_tilde_i = min(K * exp(alpha_i / temp) / sum_j exp(alpha_j / temp), 1).
+ * (The printed denominator carries the index i; it is read as the sum over j, i.e. a softmax.)
+ * The maximum is subtracted before exponentiation, which leaves the quotient unchanged.
+ */
+void ddo_soft_topk(int batch, int D, int K, double temp, const double *scores, double *alpha_tilde)
+{
+    for (int b = 0; b < batch; ++b) {
+        const double *a = scores + (int64_t)b * D;
+        double *out = alpha_tilde + (int64_t)b * D;
+        double amax = a[0];
+        for (int i = 1; i < D; ++i) if (a[i] > amax) amax = a[i];
+        double sum = 0.0;
+        for (int i = 0; i < D; ++i) sum += exp((a[i] - amax) / temp);
+        for (int i = 0; i < D; ++i) {
+            const double v = (double)K * exp((a[i] - amax) / temp) / sum;
+            out[i] = v < 1.0 ? v : 1.0;
+        }
+    }
+}
+
+/*
+ * Derivative of Eq. 5: with s = softmax(alpha / temp) and m_j = 1 where K s_j < 1 (not clamped), else 0,
+ *   dalpha_i = (K / temp) * s_i * (m_i g_i - sum_j m_j g_j s_j),   g = dL/dalpha_tilde.
+ */
+void ddo_soft_topk_bwd(int batch, int D, int K, double temp, const double *scores, const double *g,
+                       double *dscores)
+{
+    double *s = (double *)malloc(sizeof(double) * (size_t)D);
+    for (int b = 0; b < batch; ++b) {
+        const double *a = scores + (int64_t)b * D, *gb = g + (int64_t)b * D;
+        double *out = dscores + (int64_t)b * D;
+        double amax = a[0];
+        for (int i = 1; i < D; ++i) if (a[i] > amax) amax = a[i];
+        double sum = 0.0;
+        for (int i = 0; i < D; ++i) { s[i] = exp((a[i] - amax) / temp); sum += s[i]; }
+        double dot = 0.0;
+        for (int i = 0; i < D; ++i) {
+            s[i] /= sum;
+            if ((double)K * s[i] < 1.0) dot += gb[i] * s[i];
+        }
+        for (int i = 0; i < D; ++i) {
+            const double mi = (double)K * s[i] < 1.0 ? 1.0 : 0.0;
+            out[i] = (double)K / temp * s[i] * (mi * gb[i] - dot);
+        }
+    }
+    free(s);
+}
+
+/* Eq. 4: the values the products see, values_eff[k][p] = alpha_tilde[o_k mod D] * V[k][p]. */
+void ddo_scale_values(int K, int L, int D, const int32_t *offsets, const double *alpha_tilde, const double *V,
+                      double *values_eff)
+{
+    for (int k = 0; k < K; ++k) {
+        const double a = alpha_tilde[canon(offsets[k], D)];
+        for (int p = 0; p < L; ++p) values_eff[(int64_t)k * L + p] = a * V[(int64_t)k * L + p];
+    }
+}
+
+/*
+ * Its adjoint: given dValues = dL/dvalues_eff,
+ *   dV[k][p] = alpha_tilde[o_k] * dValues[k][p],   dalpha_tilde[i] = sum_{k: o_k = i} <dValues[k], V[k]>.
+ */
+void ddo_scale_values_bwd(int K, int L, int D, const int32_t *offsets, const double *alpha_tilde, const double *V,
+                          const double *dValues, double *dV, double *dalpha_tilde)
+{
+    for (int i = 0; i < D; ++i) dalpha_tilde[i] = 0.0;
+    for (int k = 0; k < K; ++k) {
+        const int64_t o = canon(offsets[k], D);
+        double dot = 0.0;
+        for (int p = 0; p < L; ++p) {
+            dV[(int64_t)k * L + p] = alpha_tilde[o] * dValues[(int64_t)k * L + p];
+            dot += dValues[(int64_t)k * L + p] * V[(int64_t)k * L + p];
+        }
+        dalpha_tilde[o] += dot;
+    }
 }

@@ -56,6 +56,18 @@ def _load():
         lib.ddo_bwd_weight_sampled.restype = None
         lib.ddo_select.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, _c_float_p, _c_int32_p]
         lib.ddo_select.restype = ctypes.c_int
+        lib.ddo_soft_topk.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double, _c_double_p,
+                                      _c_double_p]
+        lib.ddo_soft_topk.restype = None
+        lib.ddo_soft_topk_bwd.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double, _c_double_p,
+                                          _c_double_p, _c_double_p]
+        lib.ddo_soft_topk_bwd.restype = None
+        lib.ddo_scale_values.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, _c_int32_p, _c_double_p,
+                                         _c_double_p, _c_double_p]
+        lib.ddo_scale_values.restype = None
+        lib.ddo_scale_values_bwd.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, _c_int32_p, _c_double_p,
+                                             _c_double_p, _c_double_p, _c_double_p, _c_double_p]
+        lib.ddo_scale_values_bwd.restype = None
         _lib = lib
     return _lib
 
@@ -166,3 +178,51 @@ def select(scores, K):
     if _load().ddo_select(B, D, K, scores.ctypes.data_as(_c_float_p), _ip(out)):
         raise MemoryError
     return out
+
+
+def soft_topk(scores, K, temperature):
+    """alpha_tilde = min(K * softmax(scores / temperature), 1), row by row (Sec. 3.2, Eq. 5)."""
+    scores = _f64(scores)
+    if scores.ndim == 1:
+        scores = scores[None, :]
+    B, D = scores.shape
+    out = np.empty((B, D), dtype=np.float64)
+    _load().ddo_soft_topk(B, D, int(K), float(temperature), _dp(scores), _dp(out))
+    return out
+
+
+def soft_topk_bwd(scores, K, temperature, g):
+    """Gradient of the loss with respect to the scores, given g = dL/dalpha_tilde."""
+    scores = _f64(scores)
+    g = _f64(g)
+    if scores.ndim == 1:
+        scores, g = scores[None, :], g[None, :]
+    B, D = scores.shape
+    out = np.empty((B, D), dtype=np.float64)
+    _load().ddo_soft_topk_bwd(B, D, int(K), float(temperature), _dp(scores), _dp(g), _dp(out))
+    return out
+
+
+def scale_values(offsets, alpha_tilde, V):
+    """values_eff[k] = alpha_tilde[offsets[k] mod D] * V[k]  (Eq. 4)."""
+    offsets = _i32(offsets)
+    alpha_tilde = _f64(alpha_tilde)
+    V = _f64(V)
+    K, L = V.shape
+    out = np.empty((K, L), dtype=np.float64)
+    _load().ddo_scale_values(K, L, alpha_tilde.shape[0], _ip(offsets), _dp(alpha_tilde), _dp(V), _dp(out))
+    return out
+
+
+def scale_values_bwd(offsets, alpha_tilde, V, dValues):
+    """(dV [K x L], dalpha_tilde [D]) from dValues = dL/dvalues_eff."""
+    offsets = _i32(offsets)
+    alpha_tilde = _f64(alpha_tilde)
+    V = _f64(V)
+    dValues = _f64(dValues)
+    K, L = V.shape
+    D = alpha_tilde.shape[0]
+    dV = np.empty((K, L), dtype=np.float64)
+    dalpha = np.empty(D, dtype=np.float64)
+    _load().ddo_scale_values_bwd(K, L, D, _ip(offsets), _dp(alpha_tilde), _dp(V), _dp(dValues), _dp(dV), _dp(dalpha))
+    return dV, dalpha

@@ -274,3 +274,85 @@ def test_select_special_cases():
     q = np.round(s * 4) / 4  # tie-heavy
     np.testing.assert_array_equal(orc.select(q, 13), orc.select(np.exp(q.astype(np.float64)).astype(np.float32), 13))
     np.testing.assert_array_equal(orc.select(q, 13)[0], _select_numpy(q, 13))
+
+
+# ---- soft TopK weights (Sec. 3.2, Eq. 5) and the scaling of the diagonals by them (Eq. 4) ----
+
+def test_soft_topk_closed_forms():
+    # two candidates, K = 1: the softmax is a logistic function of the score difference
+    for a0, a1, T in ((0.3, -1.1, 0.7), (2.0, 2.0, 1.0), (-4.0, 1.0, 2.5)):
+        got = orc.soft_topk(np.array([a0, a1]), 1, T)[0]
+        s0 = 1.0 / (1.0 + np.exp((a1 - a0) / T))
+        np.testing.assert_allclose(got, [s0, 1.0 - s0], rtol=1e-14)
+    rng = np.random.default_rng(31)
+    a = rng.standard_normal(40)
+    # before the clamp the weights sum to K; the clamp only ever lowers them
+    for K, T in ((1, 1.0), (5, 0.5), (5, 50.0), (40, 3.0)):
+        at = orc.soft_topk(a, K, T)[0]
+        s = np.exp(a / T) / np.exp(a / T).sum()
+        np.testing.assert_allclose(at, np.minimum(K * s, 1.0), rtol=1e-13)
+        assert np.all(at <= 1.0) and np.all(at > 0.0)
+    # a constant added to every score changes nothing; a hot temperature flattens to K / D
+    np.testing.assert_allclose(orc.soft_topk(a + 123.0, 7, 0.9), orc.soft_topk(a, 7, 0.9), rtol=1e-10)
+    np.testing.assert_allclose(orc.soft_topk(a, 8, 1e9)[0], np.full(40, 8 / 40), rtol=1e-6)
+    # a cold temperature puts everything on the largest score
+    cold = orc.soft_topk(a, 3, 1e-3)[0]
+    assert cold[np.argmax(a)] == 1.0 and np.sum(cold) < 1.0 + 1e-9
+    # monotone in the score: sorting by alpha_tilde never contradicts sorting by alpha
+    at = orc.soft_topk(a, 6, 0.8)[0]
+    order = np.argsort(a)
+    assert np.all(np.diff(at[order]) >= 0)
+    # rows are independent
+    two = orc.soft_topk(np.stack([a, -a]), 6, 0.8)
+    np.testing.assert_array_equal(two[0], at)
+    np.testing.assert_array_equal(two[1], orc.soft_topk(-a, 6, 0.8)[0])
+
+
+def test_soft_topk_gradient_matches_finite_differences():
+    rng = np.random.default_rng(37)
+    D, K, T = 12, 4, 0.6
+    a = rng.standard_normal(D)
+    at = orc.soft_topk(a, K, T)[0]
+    assert np.any(at == 1.0) and np.any(at < 1.0)  # both branches of the min are exercised
+    assert np.min(np.abs(K * np.exp(a / T) / np.exp(a / T).sum() - 1.0)) > 1e-3  # no score sits on the kink
+    g = rng.standard_normal(D)
+    got = orc.soft_topk_bwd(a, K, T, g)[0]
+    h = 1e-6
+    for i in range(D):
+        e = np.zeros(D)
+        e[i] = h
+        fd = np.dot(g, orc.soft_topk(a + e, K, T)[0] - orc.soft_topk(a - e, K, T)[0]) / (2 * h)
+        assert abs(fd - got[i]) <= 1e-7 * max(1.0, abs(fd))
+
+
+def test_scale_values_and_its_adjoint():
+    rng = np.random.default_rng(41)
+    D, L, K = 10, 6, 4
+    offsets = np.array([3, -1, 13, 3])  # -1 -> 9, 13 -> 3: offset 3 is held three times
+    alpha = rng.uniform(0.1, 1.0, D)
+    V = rng.standard_normal((K, L))
+    eff = orc.scale_values(offsets, alpha, V)
+    np.testing.assert_allclose(eff, alpha[[3, 9, 3, 3]][:, None] * V, rtol=1e-15)
+    dValues = rng.standard_normal((K, L))
+    dV, dalpha = orc.scale_values_bwd(offsets, alpha, V, dValues)
+    # <dValues, alpha * V> is bilinear in (alpha, V): both gradients reproduce it
+    ref = np.sum(dValues * eff)
+    assert abs(np.sum(dV * V) - ref) <= 1e-12 * abs(ref)
+    assert abs(np.dot(dalpha, alpha) - ref) <= 1e-12 * abs(ref)
+    # entries of alpha no diagonal points at get no gradient; repeated offsets add
+    assert np.count_nonzero(dalpha) == 2
+    np.testing.assert_allclose(dalpha[3], np.sum(dValues[[0, 2, 3]] * V[[0, 2, 3]]), rtol=1e-13)
+    np.testing.assert_allclose(dalpha[9], np.sum(dValues[1] * V[1]), rtol=1e-13)
+    # chained with the layer: the loss <dY, fwd(X; alpha * V)> differentiated with respect to one alpha
+    M = N = D
+    X = rng.standard_normal((5, M))
+    dY = rng.standard_normal((5, N))
+    Vs = rng.standard_normal((K, M))
+    loss = lambda al: np.sum(dY * orc.fwd(X, offsets, orc.scale_values(offsets, al, Vs), N))
+    dValues = orc.bwd_weight(X, dY, offsets)
+    _, dalpha = orc.scale_values_bwd(offsets, alpha, Vs, dValues)
+    for i in (3, 9, 0):
+        e = np.zeros(D)
+        e[i] = 1e-4
+        fd = (loss(alpha + e) - loss(alpha - e)) / 2e-4
+        assert abs(fd - dalpha[i]) <= 1e-8 * max(1.0, abs(fd))
