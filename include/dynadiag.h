@@ -59,7 +59,13 @@ typedef enum {
     DD_ALGO_MATRIX = 2  /* W tiles rebuilt on chip and multiplied on the matrix cores       */
 } dd_algo;
 
-typedef enum { DD_OP_FWD = 0, DD_OP_BWD_INPUT = 1, DD_OP_BWD_WEIGHT = 2, DD_OP_SELECT = 3 } dd_op;
+typedef enum {
+    DD_OP_FWD = 0,
+    DD_OP_BWD_INPUT = 1,
+    DD_OP_BWD_WEIGHT = 2,
+    DD_OP_SELECT = 3,
+    DD_OP_SCALE_VALUES_BWD = 4 /* layer->K diagonals: scratch of dd_scale_values_bwd */
+} dd_op;
 
 typedef struct {
     int64_t tokens;       /* T: rows of X / dY                                   */
@@ -118,6 +124,41 @@ dd_status dd_bwd_weight(const dd_layer *layer, const void *X, const void *dY, co
  */
 dd_status dd_select_diagonals(int32_t batch, int32_t D, int32_t K, const float *scores,
                               int32_t *offsets_out, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Soft TopK weights of the D candidate diagonals (Sec. 3.2, Eq. 5; the printed denominator is read as
+ * a softmax over the candidates):
+ *   alpha_tilde[b][i] = min(K * exp(scores[b][i] / temperature) / sum_j exp(scores[b][j] / temperature), 1).
+ *   scores [batch x D] fp32 in, alpha_tilde [batch x D] fp32 out, temperature > 0 (else INVALID_ARG).
+ * The index set of the K active diagonals is still chosen by dd_select_diagonals on the raw scores
+ * (Eq. 5 is monotone in the score, so both orders agree); these weights only scale them (Eq. 4).
+ */
+dd_status dd_soft_topk(int32_t batch, int32_t D, int32_t K, float temperature, const float *scores,
+                       float *alpha_tilde, void *hip_stream);
+
+/*
+ * Derivative of dd_soft_topk: d_scores [batch x D] from d_alpha_tilde [batch x D] (both fp32); entries
+ * clamped to 1 pass no gradient.
+ */
+dd_status dd_soft_topk_bwd(int32_t batch, int32_t D, int32_t K, float temperature, const float *scores,
+                           const float *d_alpha_tilde, float *d_scores, void *hip_stream);
+
+/*
+ * The values the products see (Sec. 3.2, Eq. 4): values_eff[k][p] = alpha_tilde[offsets[k] mod D] * V[k][p].
+ *   offsets [K] int32, alpha_tilde [D] fp32, V and values_eff [K x L] of `dtype` (dd_dtype).
+ */
+dd_status dd_scale_values(int32_t K, int32_t L, int32_t D, int32_t dtype, const int32_t *offsets,
+                          const float *alpha_tilde, const void *V, void *values_eff, void *hip_stream);
+
+/*
+ * Adjoint of dd_scale_values, applied to the output of dd_bwd_weight:
+ *   dV[k][p] = alpha_tilde[o_k] * dValues[k][p]                          [K x L] fp32 out
+ *   d_alpha_tilde[i] = sum over diagonals k with o_k = i of <dValues[k], V[k]>   [D] fp32 out (0 elsewhere)
+ * Sums run in a fixed order.  ws: dd_workspace_bytes(DD_OP_SCALE_VALUES_BWD, layer with K set, 0) bytes.
+ */
+dd_status dd_scale_values_bwd(int32_t K, int32_t L, int32_t D, int32_t dtype, const int32_t *offsets,
+                              const float *alpha_tilde, const void *V, const float *dValues, float *dV,
+                              float *d_alpha_tilde, void *ws, size_t ws_bytes, void *hip_stream);
 
 const char *dd_status_string(dd_status status);
 

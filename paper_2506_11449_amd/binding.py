@@ -13,10 +13,10 @@ from .build import LIB_PATH
 
 DD_F32, DD_BF16 = 0, 1
 DD_ALGO_AUTO, DD_ALGO_VECTOR, DD_ALGO_MATRIX = 0, 1, 2
-DD_OP_FWD, DD_OP_BWD_INPUT, DD_OP_BWD_WEIGHT, DD_OP_SELECT = 0, 1, 2, 3
+DD_OP_FWD, DD_OP_BWD_INPUT, DD_OP_BWD_WEIGHT, DD_OP_SELECT, DD_OP_SCALE_VALUES_BWD = 0, 1, 2, 3, 4
 
 EXPORTS = ("dd_workspace_bytes", "dd_fwd", "dd_bwd_input", "dd_bwd_weight", "dd_select_diagonals",
-           "dd_status_string")
+           "dd_soft_topk", "dd_soft_topk_bwd", "dd_scale_values", "dd_scale_values_bwd", "dd_status_string")
 
 
 class DynaDiagError(RuntimeError):
@@ -49,7 +49,13 @@ def load_library():
     lib.dd_bwd_input.argtypes = [lp, vp, vp, vp, vp, vp, sz, vp]
     lib.dd_bwd_weight.argtypes = [lp, vp, vp, vp, vp, vp, sz, vp]
     lib.dd_select_diagonals.argtypes = [i32, i32, i32, vp, vp, vp, sz, vp]
-    for name in ("dd_fwd", "dd_bwd_input", "dd_bwd_weight", "dd_select_diagonals"):
+    f32 = ctypes.c_float
+    lib.dd_soft_topk.argtypes = [i32, i32, i32, f32, vp, vp, vp]
+    lib.dd_soft_topk_bwd.argtypes = [i32, i32, i32, f32, vp, vp, vp, vp]
+    lib.dd_scale_values.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp]
+    lib.dd_scale_values_bwd.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    for name in ("dd_fwd", "dd_bwd_input", "dd_bwd_weight", "dd_select_diagonals", "dd_soft_topk",
+                 "dd_soft_topk_bwd", "dd_scale_values", "dd_scale_values_bwd"):
         getattr(lib, name).restype = ctypes.c_int
     lib.dd_status_string.argtypes = [ctypes.c_int]
     lib.dd_status_string.restype = ctypes.c_char_p
@@ -193,3 +199,60 @@ def dd_select_diagonals(scores, K, offsets_out=None, ws=None, stream=None):
     wp, wn = _ws_for(need, scores.device, ws)
     _check(_lib.dd_select_diagonals(B, D, int(K), _ptr(scores), _ptr(offsets_out), wp, wn, _stream(stream)))
     return offsets_out
+
+
+def dd_soft_topk(scores, K, temperature, alpha_tilde=None, stream=None):
+    """alpha_tilde = min(K * softmax(scores / temperature), 1) for each row of scores [batch x D] (fp32)."""
+    B, D = scores.shape
+    _dev(scores, torch.float32, (B, D), "scores")
+    if alpha_tilde is None:
+        alpha_tilde = torch.empty_like(scores)
+    _dev(alpha_tilde, torch.float32, (B, D), "alpha_tilde")
+    _check(load_library().dd_soft_topk(B, D, int(K), float(temperature), _ptr(scores), _ptr(alpha_tilde),
+                                       _stream(stream)))
+    return alpha_tilde
+
+
+def dd_soft_topk_bwd(scores, K, temperature, d_alpha_tilde, d_scores=None, stream=None):
+    """Gradient with respect to the scores, from the gradient with respect to alpha_tilde."""
+    B, D = scores.shape
+    _dev(scores, torch.float32, (B, D), "scores")
+    _dev(d_alpha_tilde, torch.float32, (B, D), "d_alpha_tilde")
+    if d_scores is None:
+        d_scores = torch.empty_like(scores)
+    _dev(d_scores, torch.float32, (B, D), "d_scores")
+    _check(load_library().dd_soft_topk_bwd(B, D, int(K), float(temperature), _ptr(scores), _ptr(d_alpha_tilde),
+                                           _ptr(d_scores), _stream(stream)))
+    return d_scores
+
+
+def dd_scale_values(offsets, alpha_tilde, V, values_eff=None, stream=None):
+    """values_eff[k] = alpha_tilde[offsets[k] mod D] * V[k]; alpha_tilde [D] fp32, V [K x L] fp32 or bf16."""
+    K, L = V.shape
+    D = alpha_tilde.shape[0]
+    _dev(offsets, torch.int32, (K,), "offsets")
+    _dev(alpha_tilde, torch.float32, (D,), "alpha_tilde")
+    _dev(V, V.dtype, (K, L), "V")
+    if values_eff is None:
+        values_eff = torch.empty_like(V)
+    _dev(values_eff, V.dtype, (K, L), "values_eff")
+    _check(load_library().dd_scale_values(K, L, D, _DTYPES[V.dtype], _ptr(offsets), _ptr(alpha_tilde), _ptr(V),
+                                          _ptr(values_eff), _stream(stream)))
+    return values_eff
+
+
+def dd_scale_values_bwd(offsets, alpha_tilde, V, dValues, ws=None, stream=None):
+    """(dV [K x L] fp32, d_alpha_tilde [D] fp32) from dValues = the output of dd_bwd_weight."""
+    K, L = V.shape
+    D = alpha_tilde.shape[0]
+    _dev(offsets, torch.int32, (K,), "offsets")
+    _dev(alpha_tilde, torch.float32, (D,), "alpha_tilde")
+    _dev(V, V.dtype, (K, L), "V")
+    _dev(dValues, torch.float32, (K, L), "dValues")
+    dV = torch.empty((K, L), dtype=torch.float32, device=V.device)
+    d_alpha = torch.empty((D,), dtype=torch.float32, device=V.device)
+    _, _, need = _plan(DD_OP_SCALE_VALUES_BWD, 0, D, D, K, DD_F32, DD_ALGO_AUTO)
+    wp, wn = _ws_for(need, V.device, ws)
+    _check(load_library().dd_scale_values_bwd(K, L, D, _DTYPES[V.dtype], _ptr(offsets), _ptr(alpha_tilde), _ptr(V),
+                                              _ptr(dValues), _ptr(dV), _ptr(d_alpha), wp, wn, _stream(stream)))
+    return dV, d_alpha

@@ -99,6 +99,10 @@ size_t dd_workspace_bytes(int op, const dd_layer *layer, int32_t batch)
         if (!layer) return 0;
         return select_ws_bytes(batch, layer->in_features, layer->K);
     }
+    if (op == DD_OP_SCALE_VALUES_BWD) {
+        if (!layer || layer->K < 1) return 0;
+        return (size_t(layer->K) * sizeof(float) + kWsAlign - 1) / kWsAlign * kWsAlign;
+    }
     Shape s;
     if (check_layer(layer, &s) != DD_OK) return 0;
     switch (op) {
@@ -168,6 +172,57 @@ dd_status dd_select_diagonals(int32_t batch, int32_t D, int32_t K, const float *
     if (batch == 0) return DD_OK;
     if (!scores || !offsets_out) return DD_ERR_INVALID_ARG;
     return dd::launch_select(batch, D, K, scores, offsets_out, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? DD_OK
+               : DD_ERR_HIP;
+}
+
+dd_status dd_soft_topk(int32_t batch, int32_t D, int32_t K, float temperature, const float *scores,
+                       float *alpha_tilde, void *hip_stream)
+{
+    if (batch < 0 || D < 1 || K < 1 || K > D || !(temperature > 0.f)) return DD_ERR_INVALID_ARG;
+    if (batch == 0) return DD_OK;
+    if (!scores || !alpha_tilde) return DD_ERR_INVALID_ARG;
+    return dd::launch_soft_topk(batch, D, K, temperature, scores, alpha_tilde, static_cast<hipStream_t>(hip_stream)) ==
+                   hipSuccess
+               ? DD_OK
+               : DD_ERR_HIP;
+}
+
+dd_status dd_soft_topk_bwd(int32_t batch, int32_t D, int32_t K, float temperature, const float *scores,
+                           const float *d_alpha_tilde, float *d_scores, void *hip_stream)
+{
+    if (batch < 0 || D < 1 || K < 1 || K > D || !(temperature > 0.f)) return DD_ERR_INVALID_ARG;
+    if (batch == 0) return DD_OK;
+    if (!scores || !d_alpha_tilde || !d_scores) return DD_ERR_INVALID_ARG;
+    return dd::launch_soft_topk_bwd(batch, D, K, temperature, scores, d_alpha_tilde, d_scores,
+                                    static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? DD_OK
+               : DD_ERR_HIP;
+}
+
+dd_status dd_scale_values(int32_t K, int32_t L, int32_t D, int32_t dtype, const int32_t *offsets,
+                          const float *alpha_tilde, const void *V, void *values_eff, void *hip_stream)
+{
+    if (K < 1 || L < 1 || D < L || K > D || (dtype != DD_F32 && dtype != DD_BF16)) return DD_ERR_INVALID_ARG;
+    if (D > kMaxFeatures) return DD_ERR_UNSUPPORTED;
+    if (!offsets || !alpha_tilde || !V || !values_eff) return DD_ERR_INVALID_ARG;
+    return dd::launch_scale_values(K, L, D, dtype == DD_BF16, offsets, alpha_tilde, V, values_eff,
+                                   static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? DD_OK
+               : DD_ERR_HIP;
+}
+
+dd_status dd_scale_values_bwd(int32_t K, int32_t L, int32_t D, int32_t dtype, const int32_t *offsets,
+                              const float *alpha_tilde, const void *V, const float *dValues, float *dV,
+                              float *d_alpha_tilde, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (K < 1 || L < 1 || D < L || K > D || (dtype != DD_F32 && dtype != DD_BF16)) return DD_ERR_INVALID_ARG;
+    if (D > kMaxFeatures) return DD_ERR_UNSUPPORTED;
+    if (!offsets || !alpha_tilde || !V || !dValues || !dV || !d_alpha_tilde) return DD_ERR_INVALID_ARG;
+    const size_t need = (size_t(K) * sizeof(float) + kWsAlign - 1) / kWsAlign * kWsAlign;
+    if (dd_status st = check_ws(ws, ws_bytes, need)) return st;
+    return dd::launch_scale_values_bwd(K, L, D, dtype == DD_BF16, offsets, alpha_tilde, V, dValues, dV, d_alpha_tilde,
+                                       static_cast<float *>(ws), static_cast<hipStream_t>(hip_stream)) == hipSuccess
                ? DD_OK
                : DD_ERR_HIP;
 }

@@ -55,4 +55,15 @@ hipError_t launch_weight_grad_matrix(const WeightGradArgs &a, hipStream_t stream
 
 hipError_t launch_select(int batch, int D, int K, const float *scores, int *out, hipStream_t stream);
 
+// soft TopK weights and the scaling of the diagonals by them
+hipError_t launch_soft_topk(int batch, int D, int K, float temperature, const float *scores, float *alpha_tilde,
+                            hipStream_t stream);
+hipError_t launch_soft_topk_bwd(int batch, int D, int K, float temperature, const float *scores, const float *g,
+                                float *dscores, hipStream_t stream);
+hipError_t launch_scale_values(int K, int L, int D, bool bf16, const int *offsets, const float *alpha_tilde,
+                               const void *V, void *out, hipStream_t stream);
+hipError_t launch_scale_values_bwd(int K, int L, int D, bool bf16, const int *offsets, const float *alpha_tilde,
+                                   const void *V, const float *dValues, float *dV, float *dalpha, float *dots,
+                                   hipStream_t stream);
+
 }  // namespace dd

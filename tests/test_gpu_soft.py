@@ -1,0 +1,92 @@
+"""GPU parity of the soft TopK weights, their derivative and the scaling of the diagonals (Sec. 3.2,
+Eq. 4 and Eq. 5) against the CPU oracle, plus the full differentiable chain through the layer."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2506_11449_amd as dd
+from oracle import dd_oracle as orc
+from paper_2506_11449_amd import synth
+from tests.parity_util import TOL, TOL_DV, rel_err, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+TOL_SOFT = 1e-5  # fp32 exp and sums against the fp64 oracle, as max|gpu - ref| / max|ref|
+
+
+@pytest.mark.parametrize("B,D,K", [(1, 64, 8), (3, 768, 77), (2, 3072, 307), (1, 1000, 1), (2, 100, 100), (1, 5, 2)])
+@pytest.mark.parametrize("temperature", [0.05, 1.0, 30.0])
+def test_soft_topk_forward_and_backward(B, D, K, temperature):
+    scores = synth.draw_scores(B, D, seed=D + K)
+    d_scores_in = torch.from_numpy(scores).cuda()
+    at = dd.dd_soft_topk(d_scores_in, K, temperature)
+    ref = orc.soft_topk(scores, K, temperature)
+    assert rel_err(to_host(at), ref) <= TOL_SOFT
+    assert float(at.max()) <= 1.0
+    g = synth.draw_normal((B, D), 1.0, seed=9, stream=D)
+    got = to_host(dd.dd_soft_topk_bwd(d_scores_in, K, temperature, torch.from_numpy(g).cuda()))
+    ref_b = orc.soft_topk_bwd(scores, K, temperature, g)
+    # an entry whose weight sits on the clamp within fp32 resolution may fall on either side of the min
+    s = np.exp((scores.astype(np.float64) - scores.max(axis=1, keepdims=True)) / temperature)
+    s /= s.sum(axis=1, keepdims=True)
+    if np.min(np.abs(K * s - 1.0)) > 1e-4:
+        # the derivative is (K / T) s_i (g_i - sum_j g_j s_j): when one weight takes nearly everything the
+        # bracket cancels to g_i (1 - s_i), so the fp32 rounding of s_i (2^-24) leaves an absolute error of
+        # about (K / T) |g| 2^-24 whatever the size of the result; a few of those are allowed on top
+        bound = 5 * TOL_SOFT * np.max(np.abs(ref_b)) + 4 * 2.0 ** -24 * (K / temperature) * np.max(np.abs(g))
+        assert np.max(np.abs(got - ref_b)) <= bound
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("D,L,K", [(64, 64, 8), (768, 768, 77), (3072, 768, 307), (100, 52, 7)])
+def test_scale_values_and_adjoint(D, L, K, dtype):
+    rng = np.random.default_rng(D + L + K)
+    offsets = np.sort(rng.permutation(D)[:K]).astype(np.int32)
+    if K > 3:
+        offsets[1] = offsets[0]          # a repeated offset
+        offsets[2] -= D                  # a negative one
+    alpha = rng.uniform(0.0, 1.0, D).astype(np.float32)
+    V = (rng.standard_normal((K, L)) * 0.02).astype(np.float32)
+    if dtype == "bf16":
+        V = synth.round_to_bf16(V)
+    dValues = rng.standard_normal((K, L)).astype(np.float32)
+    d_off, d_alpha, d_V = torch.from_numpy(offsets).cuda(), torch.from_numpy(alpha).cuda(), to_dev(V, dtype)
+    eff = dd.dd_scale_values(d_off, d_alpha, d_V)
+    assert rel_err(to_host(eff), orc.scale_values(offsets, alpha, V)) <= TOL[dtype]
+    dV, dalpha = dd.dd_scale_values_bwd(d_off, d_alpha, d_V, torch.from_numpy(dValues).cuda())
+    ref_dV, ref_dalpha = orc.scale_values_bwd(offsets, alpha, V, dValues)
+    assert rel_err(to_host(dV), ref_dV) <= TOL_DV
+    assert rel_err(to_host(dalpha), ref_dalpha) <= TOL_DV
+    untouched = np.setdiff1d(np.arange(D), offsets % D)
+    assert np.count_nonzero(to_host(dalpha)[untouched]) == 0
+
+
+def test_differentiable_chain_scores_to_loss():
+    """scores -> soft TopK -> select -> scale -> fwd -> <dY, Y>, and back to d scores: the chain the
+    training method differentiates (Sec. 3.2), every link on the GPU, against the oracle's chain."""
+    layer = synth.WORKLOADS["tiny"][0]
+    D, L, K, N = layer.D, layer.L, layer.K, layer.out_features
+    temperature = 0.7
+    _, V, X, dY = synth.layer_inputs(layer, seed=11)
+    scores = synth.draw_scores(1, D, seed=11)
+    d_scores = torch.from_numpy(scores).cuda()
+    d_V, d_X, d_dY = to_dev(V, "f32"), to_dev(X, "f32"), to_dev(dY, "f32")
+    off = dd.dd_select_diagonals(d_scores, K)[0]
+    at = dd.dd_soft_topk(d_scores, K, temperature)[0]
+    eff = dd.dd_scale_values(off, at, d_V)
+    Y = dd.dd_fwd(d_X, off, eff, N)
+    dValues = dd.dd_bwd_weight(d_X, d_dY, off)
+    dV, dat = dd.dd_scale_values_bwd(off, at, d_V, dValues)
+    dsc = dd.dd_soft_topk_bwd(d_scores, K, temperature, dat[None, :])
+    # the same chain on the oracle
+    o_off = orc.select(scores, K)[0]
+    o_at = orc.soft_topk(scores, K, temperature)[0]
+    o_eff = orc.scale_values(o_off, o_at, V)
+    o_Y = orc.fwd(X, o_off, o_eff, N)
+    o_dValues = orc.bwd_weight(X, dY, o_off)
+    o_dV, o_dat = orc.scale_values_bwd(o_off, o_at, V, o_dValues)
+    o_dsc = orc.soft_topk_bwd(scores, K, temperature, o_dat)
+    np.testing.assert_array_equal(off.cpu().numpy(), o_off)
+    assert rel_err(to_host(Y), o_Y) <= 2e-5
+    assert rel_err(to_host(dV), o_dV) <= 2e-5
+    assert rel_err(to_host(dsc)[0], o_dsc[0]) <= 1e-4
