@@ -193,7 +193,10 @@ def main():
         achieved = dom_bytes / dom_s / 1e9
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic}
-    roofline.update({"kernel": dominant, "avg_launch_us": dom_s * 1e6, "flops_per_launch": flops_product,
+    roofline.update({"executed_on": "matrix cores (dense contraction over all D candidate diagonals)"
+                     if args.algo != "vector" and layer.dtype == "bf16" else "vector ALUs",
+                     "dense_equivalent_tflops": 2.0 * T * M * N / dom_s / 1e12,
+                     "kernel": dominant, "avg_launch_us": dom_s * 1e6, "flops_per_launch": flops_product,
                      "bytes_per_launch": dom_bytes, "flop_per_byte": intensity,
                      "achieved_tflops": flops_product / dom_s / 1e12, "achieved_gbs": dom_bytes / dom_s / 1e9})
 
@@ -205,6 +208,17 @@ def main():
                                              for k in ("dd_fwd", "dd_bwd_input", "dd_bwd_weight")},
                  "paper_context": "paper reports 3.13x inference / 1.59x training speedup at 90 % sparsity, "
                                   "ViT-Base end to end, on an A100 (abstract, Sec. 4.2.3): another machine"}
+
+    # the differentiable selection path (Sec. 3.2, Eq. 4-5), outside the timed step: launch-bound helpers
+    d_V = d_val.clone()
+    at = dd.dd_soft_topk(d_scores, K, 1.0)
+    soft = {"dd_soft_topk": time_loop(torch, lambda s: dd.dd_soft_topk(d_scores, K, 1.0, alpha_tilde=at), S, n, 5),
+            "dd_scale_values": time_loop(torch, lambda s: dd.dd_scale_values(d_off[0], at[0], d_V, values_eff=d_val),
+                                         S, n, 5),
+            "dd_scale_values_bwd": time_loop(torch, lambda s: dd.dd_scale_values_bwd(d_off[0], at[0], d_V, d_dV, ws=ws),
+                                             S, n, 5),
+            "dd_soft_topk_bwd": time_loop(torch, lambda s: dd.dd_soft_topk_bwd(d_scores, K, 1.0, at), S, n, 5)}
+    breakdown["soft_topk_path_us"] = {k: v * 1e3 for k, v in soft.items()}
 
     if not args.no_dense:
         # dense bf16 GEMMs of the same shape (hipBLASLt / rocBLAS via torch.matmul), same rotation
