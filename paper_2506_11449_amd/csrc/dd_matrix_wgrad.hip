@@ -7,14 +7,16 @@
 // (512 bf16 multiply-adds per clock per MFMA pipe against 16 on the vector ALU) this beats visiting only
 // the K diagonals down to a density of a few percent, and it reads X and dY exactly as often.
 //
-//   tile:     128 short-side x 256 long-side entries of G per workgroup (four waves, 64 x 128 each),
-//             over one chunk of tokens; chunks are summed afterwards in a fixed order (deterministic).
-//   operands: both are stored token-major, the MFMA wants the contraction index contiguous per lane, so
-//             token slices go to LDS as they are and come back through ds_read_b64_tr_b16, which hands
-//             each lane four consecutive tokens of one feature.
-//   select:   a table offset -> first diagonal with that offset (built in LDS by every workgroup while its
-//             first token slices are in flight) picks the entries of each accumulator tile; repeated
-//             offsets read the same partial sums.
+//   tile:     192 x 192 (or 128 short-side x 256 long-side) entries of G per workgroup, four waves in a 2 x 2
+//             arrangement, over one chunk of tokens; two workgroups share a CU, so that one multiplies while
+//             the other waits; chunks are summed afterwards in a fixed order (deterministic).
+//   operands: both are stored token-major while the MFMA wants the contraction index contiguous per lane, so
+//             16-token k-steps travel from global memory straight into a six-deep ring of LDS stages
+//             (global_load_lds, five k-steps ahead, no registers in between) and come back through
+//             ds_read_b64_tr_b16, which hands each lane four consecutive tokens of one feature.  Inside a
+//             k-step the fragment reads of the next one and the new requests are dealt out between the MFMAs.
+//   select:   a table (offset crossing this tile -> first diagonal with that offset) picks the entries of each
+//             accumulator tile; repeated offsets read the same partial sums.
 #include "dd_common.h"
 #include "dd_launch.h"
 
@@ -30,26 +32,76 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWgT = 256;           // threads
-constexpr int kTS = 64;             // tokens per LDS stage
-constexpr int kPad = 64;            // bytes added to every LDS row: rows of one transposing read fall on distinct banks
+constexpr int kTS = 16;             // tokens per LDS stage: one MFMA k-step
+constexpr int kSliceTokens = 32;    // token chunks are made of whole slices of two k-steps
+constexpr int kWgRing = 6;          // LDS stages: one being read, up to four on their way, one just released
+constexpr int kAhead = 5;           // a stage is requested this many k-steps before it is multiplied
 constexpr int kNoDiagonal = INT_MAX;
 constexpr int kWgXcds = 8;          // L2 caches (one per XCD); workgroups are dealt to them round-robin
 constexpr int kCusPerXcd = 32;
+constexpr int kWgPerCu = 2;         // two workgroups share a CU: one multiplies while the other waits for its slice
+
+// Sixteen bytes per lane from global memory straight into LDS: lane l of the wave lands at lds_base + 16 l.
+// lds_base is a byte address inside LDS and must be the same in every lane.  Written as assembly so that
+// the compiler does not serialise every later LDS read behind the transfer; completion is tracked by hand
+// with the vector-memory counter (transfers finish in issue order).
+__device__ __forceinline__ void global_to_lds_16(const void *g, unsigned lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(g) : "memory", "m0");
+}
+__device__ __forceinline__ unsigned lds_address(const void *p)
+{
+    return unsigned(reinterpret_cast<size_t>((__attribute__((address_space(3))) const char *)(p)));
+}
+
+// What the transfers of short-side rows past the end of a chunk read instead: a zero factor adds nothing.
+__device__ __align__(16) const unsigned int wg_zero_piece[4] = {0u, 0u, 0u, 0u};
 
 // Tile of G per workgroup: TP short-side x TQ long-side entries, four waves in a 2 x 2 arrangement.
+// A stage holds kTS tokens: first their TP short-side features (row = token), then their TQ long-side ones.
 template <int TP, int TQ>
 struct WgTile {
     static constexpr int FA = TP / 64;             // 32-row MFMA tiles per wave
     static constexpr int FB = TQ / 64;             // 32-column MFMA tiles per wave
-    static constexpr int ARow = TP * 2 + kPad;
-    static constexpr int BRow = TQ * 2 + kPad;
+    static constexpr int ARow = TP * 2;            // bytes
+    static constexpr int BRow = TQ * 2;
     static constexpr int ABytes = kTS * ARow;
     static constexpr int BBytes = kTS * BRow;
     static constexpr int StageBytes = ABytes + BBytes;
-    static constexpr int AChunks = kTS * (TP / 8) / kWgT;   // 16-byte pieces per thread per stage
-    static constexpr int BChunks = kTS * (TQ / 8) / kWgT;
+    static constexpr int APieces = ABytes / 16;          // 16-byte pieces of a stage
+    static constexpr int Rounds = StageBytes / 16 / kWgT;   // pieces per thread per stage
+    static constexpr int Window = TP + TQ;         // offsets (column - row) that cross the tile: Window - 1 of them
+    static constexpr int LdsBytes = kWgRing * StageBytes + Window * int(sizeof(int));
+    static constexpr int NM = FA * FB;             // MFMAs per k-step
+    static constexpr int NF = FA + FB;             // fragments per k-step
     static_assert(TP % 64 == 0 && TQ % 64 == 0, "wave tiles are made of 32x32 MFMA tiles");
+    static_assert(StageBytes % (16 * kWgT) == 0, "a stage is moved in whole rounds of the workgroup");
 };
+
+// Order of work inside a k-step.  Fragments are fetched A0, B0, A1, B1, ... and the MFMAs are taken in the
+// order in which their fragments arrive: by max(a, b).
+template <int FA, int FB>
+struct WgOrder {
+    int mfma_a[FA * FB], mfma_b[FA * FB];
+    int frag_is_a[FA + FB], frag_idx[FA + FB];
+    constexpr WgOrder() : mfma_a(), mfma_b(), frag_is_a(), frag_idx()
+    {
+        int n = 0;
+        for (int level = 0; level < (FA > FB ? FA : FB); ++level)
+            for (int a = 0; a < FA; ++a)
+                for (int b = 0; b < FB; ++b)
+                    if ((a > b ? a : b) == level) { mfma_a[n] = a; mfma_b[n] = b; ++n; }
+        int k = 0;
+        for (int i = 0; i < (FA > FB ? FA : FB); ++i) {
+            if (i < FA) { frag_is_a[k] = 1; frag_idx[k] = i; ++k; }
+            if (i < FB) { frag_is_a[k] = 0; frag_idx[k] = i; ++k; }
+        }
+    }
+};
+
+// Rows are not padded; instead the 16-byte pieces of row r are permuted by XOR with 2 * (r mod 4), so that
+// the four rows one transposing read touches fall on four different 32-byte bank groups.
+__device__ __forceinline__ int wg_swizzle(int row) { return (row & 3) << 1; }
 
 __device__ __forceinline__ bf16x8 read_transposed(const unsigned char *p0, const unsigned char *p1)
 {
@@ -63,18 +115,21 @@ __device__ __forceinline__ bf16x8 read_transposed(const unsigned char *p0, const
 
 // partial[split][k][p] for the representatives k of this tile's active offsets
 template <int TP, int TQ>
-__global__ __launch_bounds__(kWgT) void wgrad_mm_kernel(int T, int D, int L, int K, int tiles_p, int tiles_q,
-                                                        int splits, int slices,
-                                                        const uint16_t *__restrict__ A,
-                                                        const uint16_t *__restrict__ B,
-                                                        const int *__restrict__ offsets, float *__restrict__ partial)
+__global__ __launch_bounds__(kWgT, kWgPerCu) void wgrad_mm_kernel(int T, int D, int L, int K, int tiles_p,
+                                                                  int tiles_q, int splits, int slices,
+                                                                  const uint16_t *__restrict__ A,
+                                                                  const uint16_t *__restrict__ B,
+                                                                  const int *__restrict__ offsets,
+                                                                  float *__restrict__ partial)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     using Tl = WgTile<TP, TQ>;
     constexpr int kARow = Tl::ARow, kBRow = Tl::BRow, kABytes = Tl::ABytes, kStageBytes = Tl::StageBytes;
-    constexpr int kAChunks = Tl::AChunks, kBChunks = Tl::BChunks, kTP = TP, kTQ = TQ;
-    int *table = reinterpret_cast<int *>(smem + 2 * kStageBytes);  // [D]: offset -> first diagonal, or kNoDiagonal
+    int *table = reinterpret_cast<int *>(smem + kWgRing * kStageBytes);  // [Window]: offset -> first diagonal
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // Every kernel argument is brought into registers now: a scalar load still pending inside the main loop
+    // would force each wait for LDS data to wait for everything outstanding.
+    asm volatile("" ::"s"(partial), "s"(offsets), "s"(A), "s"(B), "s"(K), "s"(L));
     // Token chunks are dealt to the XCDs: every tile of one chunk runs on the same L2, so the chunk's
     // slices of X and dY come from HBM once and from that L2 for every other tile.
     const int tiles = tiles_p * tiles_q;
@@ -82,68 +137,66 @@ __global__ __launch_bounds__(kWgT) void wgrad_mm_kernel(int T, int D, int L, int
     const int split = (local / tiles) * kWgXcds + xcd;
     if (split >= splits) return;
     const int tile = local % tiles;
-    const int p0 = (tile / tiles_q) * kTP, q0 = (tile % tiles_q) * kTQ;
-    // chunk `split` owns the 64-token slices [split * slices / splits, (split + 1) * slices / splits)
+    const int p0 = (tile / tiles_q) * TP, q0 = (tile % tiles_q) * TQ;
+    // chunk `split` owns the 32-token slices [split * slices / splits, (split + 1) * slices / splits)
     const int slice_begin = int(int64_t(split) * slices / splits), slice_end = int(int64_t(split + 1) * slices / splits);
-    const int t_begin = slice_begin * kTS;
-    const int t_end = min(slice_end * kTS, T);
-    const int n_slices = slice_end - slice_begin;
+    const int t_begin = slice_begin * kSliceTokens;
+    const int t_end = min(slice_end * kSliceTokens, T);
+    const int n_steps = (slice_end - slice_begin) * (kSliceTokens / kTS);  // even, at least 2
 
-
-    // global -> register -> LDS staging.  A piece is 8 features of one token.
-    int a_row[kAChunks], a_col[kAChunks], b_row[kBChunks], b_col[kBChunks];
+    // Memory -> LDS without passing through registers: in round i the workgroup moves pieces
+    // [i * 256, i * 256 + 256) of the stage, each wave a contiguous kilobyte (lane l lands at +16 l).
+    // Which piece of global memory a lane asks for is what realises the swizzle.
+    const uint16_t *src_col[Tl::Rounds];  // column part of the address
+    int src_row[Tl::Rounds];              // token of the piece in k-step 0
+    int src_ld[Tl::Rounds];               // row pitch of the matrix the piece comes from
 #pragma unroll
-    for (int n = 0; n < kAChunks; ++n) {
-        const int idx = tid + kWgT * n;
-        a_row[n] = idx / (kTP / 8);
-        a_col[n] = (idx % (kTP / 8)) * 8;
+    for (int i = 0; i < Tl::Rounds; ++i) {
+        const int piece_all = i * kWgT + tid;
+        const bool is_a = piece_all < Tl::APieces;
+        const int piece = is_a ? piece_all : piece_all - Tl::APieces;
+        const int per_row = (is_a ? TP : TQ) / 8;
+        const int row = piece / per_row, pos = piece % per_row;
+        const int col = (pos ^ wg_swizzle(row)) * 8;
+        src_col[i] = is_a ? A + p0 + col : B + q0 + col;
+        src_row[i] = t_begin + row;
+        src_ld[i] = is_a ? L : D;
     }
-#pragma unroll
-    for (int n = 0; n < kBChunks; ++n) {
-        const int idx = tid + kWgT * n;
-        b_row[n] = idx / (kTQ / 8);
-        b_col[n] = (idx % (kTQ / 8)) * 8;
-    }
-    const uint16_t *a_base[kAChunks], *b_base[kBChunks];
-#pragma unroll
-    for (int n = 0; n < kAChunks; ++n) a_base[n] = A + p0 + a_col[n];
-#pragma unroll
-    for (int n = 0; n < kBChunks; ++n) b_base[n] = B + q0 + b_col[n];
-    u32x4 ag0[kAChunks], bg0[kBChunks], ag1[kAChunks], bg1[kBChunks];
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
-    // Rows past the end of the chunk must add nothing: their short-side piece is replaced by zeros (one
-    // zero factor is enough); the loads themselves stay in bounds by re-reading the last token.
-#define DD_WG_LOAD(ag_, bg_, s_)                                                                        \
+    const unsigned lds_stage0 = __builtin_amdgcn_readfirstlane(lds_address(smem) + wave * 1024);
+    // Rows past the end of the chunk must add nothing: their pieces come from a block of zeros instead.  The
+    // same holds for whole k-steps past the end, which are requested like any other so that the count of
+    // transfers in flight is the same in every iteration.
+#define DD_WG_ISSUE_PIECE(i_, s_, stage_)                                                                \
     {                                                                                                   \
-        const int tb = t_begin + (s_) * kTS;                                                            \
-        _Pragma("unroll") for (int n = 0; n < kAChunks; ++n) {                                          \
-            const int t = tb + a_row[n];                                                                \
-            const u32x4 v = *reinterpret_cast<const u32x4 *>(a_base[n] + size_t(min(t, T - 1)) * L);    \
-            ag_[n] = t < t_end ? v : zero4;                                                             \
-        }                                                                                               \
-        _Pragma("unroll") for (int n = 0; n < kBChunks; ++n) {                                          \
-            const int t = min(tb + b_row[n], T - 1);                                                    \
-            bg_[n] = *reinterpret_cast<const u32x4 *>(b_base[n] + size_t(t) * D);                       \
-        }                                                                                               \
+        const int t = src_row[i_] + (s_) * kTS;                                                         \
+        const uint16_t *g = src_col[i_] + size_t(t) * size_t(src_ld[i_]);                               \
+        if (t >= t_end) g = reinterpret_cast<const uint16_t *>(wg_zero_piece);                          \
+        global_to_lds_16(g, lds_stage0 + (stage_) * kStageBytes + (i_) * (kWgT * 16));                  \
     }
-#define DD_WG_STORE(ag_, bg_, buf_)                                                                     \
-    {                                                                                                   \
-        unsigned char *base = smem + (buf_) * kStageBytes;                                              \
-        _Pragma("unroll") for (int n = 0; n < kAChunks; ++n)                                            \
-            *reinterpret_cast<u32x4 *>(base + a_row[n] * kARow + a_col[n] * 2) = ag_[n];                \
-        _Pragma("unroll") for (int n = 0; n < kBChunks; ++n)                                            \
-            *reinterpret_cast<u32x4 *>(base + kABytes + b_row[n] * kBRow + b_col[n] * 2) = bg_[n];      \
-    }
+#define DD_WG_ISSUE(s_, stage_)                                                                          \
+    _Pragma("unroll") for (int i = 0; i < Tl::Rounds; ++i) DD_WG_ISSUE_PIECE(i, s_, stage_)
+    // all but the newest `n_` of this wave's transfers have landed; then the same for the whole workgroup
+#define DD_WG_ARRIVE(n_) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(n_) : "memory")
+#define DD_WG_LDS_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
 
     // Fragment addressing.  In a group of 16 lanes, lane s supplies row s/4 (a token) and features
     // 4*(s%4)..+3; it receives feature s of the group for those four tokens.  Groups 0,1 cover features
     // 0-15 / 16-31 of the first 8 tokens of a k-step, groups 2,3 the same features of the last 8.
     const int s16 = lane & 15, grp = lane >> 4;
-    const int frag_row = (grp >> 1) * 8 + (s16 >> 2);
+    const int frag_row = (grp >> 1) * 8 + (s16 >> 2);     // and frag_row + 4; both have row mod 4 = s16 / 4
     const int frag_col = (grp & 1) * 16 + (s16 & 3) * 4;
     const int wp = wave >> 1, wq = wave & 1;     // wave tile: rows wp*TP/2.., columns wq*TQ/2..
-    const int a_frag = frag_row * kARow + (wp * (TP / 2) + frag_col) * 2;
-    const int b_frag = kABytes + frag_row * kBRow + (wq * (TQ / 2) + frag_col) * 2;
+    int a_frag[Tl::FA], b_frag[Tl::FB];
+#pragma unroll
+    for (int a = 0; a < Tl::FA; ++a) {
+        const int col = wp * (TP / 2) + a * 32 + frag_col;
+        a_frag[a] = frag_row * kARow + (((col >> 3) ^ wg_swizzle(frag_row)) << 4) + (col & 7) * 2;
+    }
+#pragma unroll
+    for (int b = 0; b < Tl::FB; ++b) {
+        const int col = wq * (TQ / 2) + b * 32 + frag_col;
+        b_frag[b] = kABytes + frag_row * kBRow + (((col >> 3) ^ wg_swizzle(frag_row)) << 4) + (col & 7) * 2;
+    }
 
     f32x16 acc[Tl::FA][Tl::FB];
 #pragma unroll
@@ -153,15 +206,14 @@ __global__ __launch_bounds__(kWgT) void wgrad_mm_kernel(int T, int D, int L, int
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-#define DD_WG_FRAGS(fa_, fb_, buf_, ks_)                                                                 \
+#define DD_WG_FRAGS(fa_, fb_, base_)                                                                \
     {                                                                                                   \
-        const unsigned char *base = smem + (buf_) * kStageBytes;                                        \
         _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a) {                                            \
-            const unsigned char *p = base + a_frag + (ks_) * 16 * kARow + a * 64;                       \
+            const unsigned char *p = (base_) + a_frag[a];                                               \
             fa_[a] = read_transposed(p, p + 4 * kARow);                                                 \
         }                                                                                               \
         _Pragma("unroll") for (int b = 0; b < Tl::FB; ++b) {                                            \
-            const unsigned char *p = base + b_frag + (ks_) * 16 * kBRow + b * 64;                       \
+            const unsigned char *p = (base_) + b_frag[b];                                               \
             fb_[b] = read_transposed(p, p + 4 * kBRow);                                                 \
         }                                                                                               \
     }
@@ -169,120 +221,189 @@ __global__ __launch_bounds__(kWgT) void wgrad_mm_kernel(int T, int D, int L, int
     _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a)                                                  \
         _Pragma("unroll") for (int b = 0; b < Tl::FB; ++b)                                              \
             acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa_[a], fb_[b], acc[a][b], 0, 0, 0);
-    // four k-steps of one slice; the fragments of the next k-step are fetched while the current one multiplies
-#define DD_WG_COMPUTE(buf_)                                                                             \
-    DD_WG_FRAGS(fa0, fb0, buf_, 0)                                                                      \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_WG_FRAGS(fa1, fb1, buf_, 1)                                                                      \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_WG_MFMA(fa0, fb0)                                                                                \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_WG_FRAGS(fa0, fb0, buf_, 2)                                                                      \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_WG_MFMA(fa1, fb1)                                                                                \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_WG_FRAGS(fa1, fb1, buf_, 3)                                                                      \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_WG_MFMA(fa0, fb0)                                                                                \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_WG_MFMA(fa1, fb1)
     bf16x8 fa0[Tl::FA], fb0[Tl::FB], fa1[Tl::FA], fb1[Tl::FB];
 
-    // Two slices in flight in registers, two LDS buffers, one barrier per slice; slices are taken in pairs,
-    // an odd last one on its own.  The offset table is filled in LDS while the first slices travel.
-    DD_WG_LOAD(ag0, bg0, 0)
-    DD_WG_LOAD(ag1, bg1, 1)
-    for (int i = tid; i < D; i += kWgT) table[i] = kNoDiagonal;
-    __syncthreads();
-    for (int k = tid; k < K; k += kWgT) atomicMin(&table[canonical_offset(offsets[k], D)], k);
-    DD_WG_STORE(ag0, bg0, 0)
-    __syncthreads();
-    for (int s = 0; s + 1 < n_slices; s += 2) {
-        DD_WG_LOAD(ag0, bg0, s + 2)
-        __builtin_amdgcn_sched_barrier(0);
-        DD_WG_COMPUTE(0)
-        __builtin_amdgcn_sched_barrier(0);
-        DD_WG_STORE(ag1, bg1, 1)
-        __syncthreads();
-        DD_WG_LOAD(ag1, bg1, s + 3)
-        __builtin_amdgcn_sched_barrier(0);
-        DD_WG_COMPUTE(1)
-        __builtin_amdgcn_sched_barrier(0);
-        DD_WG_STORE(ag0, bg0, 0)
-        __syncthreads();
+    // The offsets are requested before the token slices and looked at after the main loop.
+    const int window_base = q0 - p0 - TP + 1;
+    constexpr int kMaxOwn = 4;
+    int own[kMaxOwn];
+#pragma unroll
+    for (int j = 0; j < kMaxOwn; ++j) {
+        const int k = tid + j * kWgT;
+        own[j] = k < K ? offsets[k] : 0;
     }
-    if (n_slices & 1) {  // uniform over the workgroup; the last slice sits in buffer 0
-        DD_WG_COMPUTE(0)
-        __syncthreads();
+    // k-step j_: wait until j_+1 has landed for every wave (every wave is then also done with j_-1, whose
+    // stage is requested for j_+kAhead), and multiply the fragments of j_.  The fragment reads of j_+1 and
+    // the new requests are dealt out one after each MFMA, so that they issue while the matrix pipe is busy.
+#define DD_WG_STEP(j_, cur_a_, cur_b_, nxt_a_, nxt_b_)                                                   \
+    {                                                                                                   \
+        DD_WG_ARRIVE((kAhead - 2) * Tl::Rounds);                                                        \
+        const int next_stage = stage == kWgRing - 1 ? 0 : stage + 1;                                    \
+        const int ahead = stage == 0 ? kWgRing - 1 : stage - 1; /* (stage + kAhead) mod kWgRing */      \
+        const unsigned char *base = smem + next_stage * kStageBytes;                                    \
+        _Pragma("unroll") for (int m = 0; m < Tl::NM; ++m) {                                            \
+            const int a = kOrder.mfma_a[m], b = kOrder.mfma_b[m];                                       \
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_a_[a], cur_b_[b], acc[a][b], 0, 0, 0); \
+            __builtin_amdgcn_sched_barrier(0);                                                          \
+            _Pragma("unroll") for (int k = 0; k < Tl::NF + Tl::Rounds; ++k) {                           \
+                if ((k < Tl::NM ? k : Tl::NM - 1) != m) continue;                                       \
+                if (k < Tl::NF) {                                                                       \
+                    const int f = kOrder.frag_idx[k];                                                   \
+                    if (kOrder.frag_is_a[k]) {                                                          \
+                        const unsigned char *p = base + a_frag[f];                                      \
+                        nxt_a_[f] = read_transposed(p, p + 4 * kARow);                                  \
+                    } else {                                                                            \
+                        const unsigned char *p = base + b_frag[f];                                      \
+                        nxt_b_[f] = read_transposed(p, p + 4 * kBRow);                                  \
+                    }                                                                                   \
+                } else {                                                                                \
+                    DD_WG_ISSUE_PIECE(k - Tl::NF, (j_) + kAhead, ahead)                                 \
+                }                                                                                       \
+            }                                                                                           \
+            __builtin_amdgcn_sched_barrier(0);                                                          \
+        }                                                                                               \
+        stage = next_stage;                                                                             \
     }
-#undef DD_WG_LOAD
-#undef DD_WG_STORE
-#undef DD_WG_COMPUTE
+    static_assert(kAhead == kWgRing - 1, "the stage requested at k-step j is the one k-step j-1 has just left");
+    constexpr WgOrder<Tl::FA, Tl::FB> kOrder{};
+#pragma unroll
+    for (int j = 0; j < kAhead; ++j) DD_WG_ISSUE(j, j)
+    for (int i = tid; i < Tl::Window; i += kWgT) table[i] = kNoDiagonal;  // filled in after the main loop
+    DD_WG_ARRIVE((kAhead - 1) * Tl::Rounds);
+    DD_WG_FRAGS(fa0, fb0, smem)
+    int stage = 0;
+    int j = 0;
+    for (; j < n_steps - 2; j += 2) {
+        DD_WG_STEP(j, fa0, fb0, fa1, fb1)
+        DD_WG_STEP(j + 1, fa1, fb1, fa0, fb0)
+    }
+    DD_WG_STEP(j, fa0, fb0, fa1, fb1)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the requests past the end have to land before the stages are reused
+    DD_WG_MFMA(fa1, fb1)
+#undef DD_WG_STEP
+    // The table of the offsets that cross this tile: entry e stands for (column - row) = q0 - p0 - TP + 1 + e
+    // (mod D) and holds the first diagonal with that offset.  (Cleared before the main loop; the barriers of
+    // the loop lie between.)
+#define DD_WG_ENTER(o_, k_)                                                                              \
+    {                                                                                                   \
+        int e = canonical_offset(o_, D) - window_base;                                                  \
+        e = e < 0 ? e + D : (e >= D ? e - D : e);                                                       \
+        if (e < Tl::Window - 1) atomicMin(&table[e], k_);                                               \
+    }
+#pragma unroll
+    for (int j = 0; j < kMaxOwn; ++j)
+        if (tid + j * kWgT < K) DD_WG_ENTER(own[j], tid + j * kWgT)
+    for (int k = tid + kMaxOwn * kWgT; k < K; k += kWgT) DD_WG_ENTER(offsets[k], k)
+#undef DD_WG_ENTER
+    DD_WG_LDS_BARRIER();  // the table is complete and every wave is done with the stages: they become tile buffers
+#undef DD_WG_ISSUE
+#undef DD_WG_ARRIVE
 #undef DD_WG_FRAGS
 #undef DD_WG_MFMA
 
-    // Keep the entries on active diagonals, one 32x32 accumulator tile at a time.  Accumulator i of lane l
-    // is row 8*(i/4) + 4*(l/32) + i%4, column l%32 of the tile.  The tile is laid out column-major in a
-    // small LDS buffer of the wave's own; the 63 offsets that cross it are looked up at once (one per
-    // lane); every active one is then read back along the diagonal, lane = row, so that the partial sums
-    // of one diagonal leave as one contiguous run.  (The loop's last barrier retired all stage reads.)
+    // Keep the entries on active diagonals.  Accumulator i of lane l is row 8*(i/4) + 4*(l/32) + i%4, column
+    // l%32 of its 32x32 tile.  Tiles are handled three at a time to overlap their LDS round trips: each is
+    // laid out column-major in a buffer of the wave's own; the 63 offsets that cross it were looked up in the
+    // table (one per lane) and the active ones are compacted into a list; then eight diagonals are read back
+    // at once along the diagonal -- lane = (list slot, row mod 8) -- and leave as 32-byte runs of partial sums.
     constexpr int kTileStride = 36;  // floats per tile column: 16-byte aligned rows of four, odd diagonal stride
-    float *tilebuf = reinterpret_cast<float *>(smem) + wave * (32 * kTileStride);
+    constexpr int kTileFloats = 32 * kTileStride;
+    constexpr int kGroup = 3;
+    constexpr int kTilesPerWave = Tl::FA * Tl::FB;
+    constexpr int kWaveBytes = kWgRing * kStageBytes / 4;
+    static_assert(kGroup * kTileFloats * 4 + kTilesPerWave * 64 * 4 <= kWaveBytes, "tile buffers and lists fit the wave's share of the stages");
+    float *tilebuf = reinterpret_cast<float *>(smem + wave * kWaveBytes);                 // [kGroup][32 x 36]
+    int *lists = reinterpret_cast<int *>(smem + wave * kWaveBytes) + kGroup * kTileFloats;  // [tiles][64]
     float *out = partial + size_t(split) * K * L;
     const int l32 = lane & 31, half = lane >> 5;
+    const int slot = lane >> 3, rmod = lane & 7;
+    // lane j < 63 of tile t: first diagonal with (column - row) = j - 31, if any; the active ones are ranked
+    // and entered into the tile's list as (diagonal << 6 | j)
+    int n_active[kTilesPerWave], kj[kTilesPerWave];
 #pragma unroll
-    for (int a = 0; a < Tl::FA; ++a)
+    for (int t = 0; t < kTilesPerWave; ++t) {
+        const int pl = wp * (TP / 2) + (t / Tl::FB) * 32, ql = wq * (TQ / 2) + (t % Tl::FB) * 32;
+        int e = ql - pl + lane - 31 + TP - 1;  // in [0, Window - 1]
+        e = e >= D ? e - D : e;                // a window wider than D wraps onto itself
+        kj[t] = table[e];
+    }
 #pragma unroll
-        for (int b = 0; b < Tl::FB; ++b) {
-            const int pb = p0 + wp * (TP / 2) + a * 32, qb = q0 + wq * (TQ / 2) + b * 32;
+    for (int t = 0; t < kTilesPerWave; ++t) {
+        const bool mine = kj[t] != kNoDiagonal && lane < 63;
+        const unsigned long long active = __ballot(mine);
+        n_active[t] = __popcll(active);
+        const int rank = __builtin_amdgcn_mbcnt_hi(unsigned(active >> 32), __builtin_amdgcn_mbcnt_lo(unsigned(active), 0u));
+        lists[t * 64 + (mine ? rank : 63)] = (kj[t] << 6) | lane;  // at most 63 are active: slot 63 takes the rest
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    int entry[kTilesPerWave];
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const f32x4 v = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
-                *reinterpret_cast<f32x4 *>(tilebuf + l32 * kTileStride + 8 * g + 4 * half) = v;
-            }
-            // lane j < 63 looks up the diagonal with (column - row) = j - 31 inside this tile
-            int delta = qb - pb + lane - 31;
-            delta = delta < 0 ? delta + D : (delta >= D ? delta - D : delta);
-            const int kj = lane < 63 ? table[delta] : kNoDiagonal;
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            unsigned long long active = __ballot(kj != kNoDiagonal);
-            // four diagonals per round, two per half-wave, so that their LDS reads overlap
-            while (active) {
-                int j[4], kk[4];
+    for (int t = 0; t < kTilesPerWave; ++t) entry[t] = lists[t * 64 + slot];
+    // Values of list entry e_ of the tile in buffer g_ on rows rmod + 8 i.  col_ = row + (column - row) of the
+    // entry, or something far outside the tile when the lane's list slot is empty; the read itself is always
+    // in bounds (column clamped), the store is predicated on the column being inside the tile.
+#define DD_WG_DIAG_LOAD(v_, col_, g_, e_, have_)                                                         \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                     \
+        col_[i] = unsigned(rmod + 8 * i + ((have_) ? ((e_) & 63) - 31 : 64));                           \
+        v_[i] = tilebuf[(g_) * kTileFloats + int(min(col_[i], 31u)) * kTileStride + rmod + 8 * i];      \
+    }
+#define DD_WG_DIAG_STORE(v_, col_, t_, e_)                                                               \
+    {                                                                                                   \
+        const unsigned byte0 = (unsigned((e_) >> 6) * unsigned(L) + unsigned(p0 + wp * (TP / 2) + ((t_) / Tl::FB) * 32 + rmod)) * 4u; \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                   \
+            if (col_[i] < 32u)                                                         \
+                *reinterpret_cast<float *>(reinterpret_cast<char *>(out) + (byte0 + 32u * i)) = v_[i];  \
+    }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    j[u] = active ? __builtin_ctzll(active) : 63;  // lane 63 never holds a diagonal
-                    active &= active - 1;                          // no-op once empty
-                    kk[u] = __builtin_amdgcn_readlane(kj, j[u]);
+    for (int t0 = 0; t0 < kTilesPerWave; t0 += kGroup) {
+#pragma unroll
+        for (int g = 0; g < kGroup; ++g) {
+            const int t = t0 + g;
+            if (t < kTilesPerWave) {
+                const int a = t / Tl::FB, b = t % Tl::FB;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f32x4 v = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
+                    *reinterpret_cast<f32x4 *>(tilebuf + g * kTileFloats + l32 * kTileStride + 8 * q + 4 * half) = v;
                 }
-                float v[2];
-                int kd[2];
-                bool ok[2];
-#pragma unroll
-                for (int uu = 0; uu < 2; ++uu) {
-                    const int jj = half ? j[2 * uu + 1] : j[2 * uu];
-                    kd[uu] = half ? kk[2 * uu + 1] : kk[2 * uu];
-                    const int col = l32 + jj - 31;  // column of this lane's row on that diagonal
-                    ok[uu] = kd[uu] != kNoDiagonal && col >= 0 && col < 32;
-                    v[uu] = ok[uu] ? tilebuf[col * kTileStride + l32] : 0.f;
-                }
-#pragma unroll
-                for (int uu = 0; uu < 2; ++uu)
-                    if (ok[uu]) out[unsigned(kd[uu]) * unsigned(L) + unsigned(pb + l32)] = v[uu];
             }
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        float v[kGroup][4];
+        unsigned col[kGroup][4];
+#pragma unroll
+        for (int g = 0; g < kGroup; ++g)
+            if (t0 + g < kTilesPerWave) DD_WG_DIAG_LOAD(v[g], col[g], g, entry[t0 + g], slot < n_active[t0 + g])
+#pragma unroll
+        for (int g = 0; g < kGroup; ++g)
+            if (t0 + g < kTilesPerWave) DD_WG_DIAG_STORE(v[g], col[g], t0 + g, entry[t0 + g])
+#pragma unroll
+        for (int g = 0; g < kGroup; ++g)  // more than eight diagonals across one tile: rare at the paper's sparsities
+            if (t0 + g < kTilesPerWave)
+                for (int first = 8; first < n_active[t0 + g]; first += 8) {
+                    const int e = lists[(t0 + g) * 64 + ((first + slot) & 63)];
+                    DD_WG_DIAG_LOAD(v[g], col[g], g, e, first + slot < n_active[t0 + g])
+                    DD_WG_DIAG_STORE(v[g], col[g], t0 + g, e)
+                }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+#undef DD_WG_DIAG_LOAD
+#undef DD_WG_DIAG_STORE
 }
 
-// dV[k][p] = sum over splits, in order, of partial[split][rep(k)][p], rep(k) = first diagonal with k's offset
+// dV[k][p] = sum over the chunks of partial[chunk][rep(k)][p], rep(k) = first diagonal with k's offset.  The
+// chunks are cut into four runs that four groups of threads add up side by side, each in chunk order; the four
+// sums are then added in run order: a fixed order, so the result is the same on every call.
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(int D, int L, int K, int splits,
                                                            const int *__restrict__ offsets,
                                                            const float *__restrict__ partial,
                                                            float *__restrict__ dV)
 {
     __shared__ int rep_s;
+    __shared__ f32x4 run_s[3][64];
     const int k = blockIdx.y;
     if (threadIdx.x == 0) rep_s = k;
     __syncthreads();
@@ -291,11 +412,34 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(int D, int L, int K, 
         if (canonical_offset(offsets[j], D) == mine) atomicMin(&rep_s, j);
     __syncthreads();
     const int rep = rep_s;
-    const int p = blockIdx.x * 256 + threadIdx.x;
-    if (p >= L) return;
-    float acc = 0.f;
-    for (int s = 0; s < splits; ++s) acc += partial[(size_t(s) * K + rep) * L + p];
-    dV[size_t(k) * L + p] = acc;
+    const int run = threadIdx.x >> 6, g = threadIdx.x & 63;
+    const int p = blockIdx.x * 256 + g * 4;  // L is a multiple of 64
+    const int per_run = (splits + 3) / 4;
+    const int s_begin = min(run * per_run, splits), s_end = min(s_begin + per_run, splits);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    if (p < L) {
+        const size_t stride = size_t(K) * L;
+        const float *src = partial + (size_t(s_begin) * K + rep) * L + p;
+        int s = s_begin;
+        for (; s + 8 <= s_end; s += 8) {  // eight loads in flight
+            f32x4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x4 *>(src + u * stride);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += v[u];
+            src += 8 * stride;
+        }
+        for (; s < s_end; ++s) {
+            acc += *reinterpret_cast<const f32x4 *>(src);
+            src += stride;
+        }
+    }
+    if (run > 0) run_s[run - 1][g] = acc;
+    __syncthreads();
+    if (run == 0 && p < L) {
+        acc = ((acc + run_s[0][g]) + run_s[1][g]) + run_s[2][g];
+        *reinterpret_cast<f32x4 *>(dV + size_t(k) * L + p) = acc;
+    }
 }
 
 // ---- host side ----
@@ -317,10 +461,10 @@ static WgradPlan plan_wgrad(int64_t T, int D, int L)
     pl.tiles_q = D / pl.tq;
     const int tiles = pl.tiles_p * pl.tiles_q;
     // chunks per XCD: as many as fill its 32 CUs in one round
-    int per_xcd = kCusPerXcd / tiles;
+    int per_xcd = kCusPerXcd * kWgPerCu / tiles;
     if (per_xcd < 1) per_xcd = 1;
     int64_t splits = int64_t(per_xcd) * kWgXcds;
-    const int64_t slices = (T + kTS - 1) / kTS;
+    const int64_t slices = (T + kSliceTokens - 1) / kSliceTokens;
     if (splits > slices) splits = slices;
     pl.slices = int(slices);
     pl.splits = int(splits);
@@ -349,11 +493,11 @@ static hipError_t launch_wgrad_mm(const WeightGradArgs &a, const WgradPlan &pl, 
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_mm_kernel<TP, TQ>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           2 * Tl::StageBytes + 8192 * int(sizeof(int)));
+                                           Tl::LdsBytes);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    const int lds_bytes = 2 * Tl::StageBytes + a.D * int(sizeof(int));
+    const int lds_bytes = Tl::LdsBytes;
     hipLaunchKernelGGL((wgrad_mm_kernel<TP, TQ>), dim3(pl.grid), dim3(kWgT), lds_bytes, stream, int(a.T), a.D, a.L,
                        a.K, pl.tiles_p, pl.tiles_q, pl.splits, pl.slices,
                        static_cast<const uint16_t *>(a.A), static_cast<const uint16_t *>(a.B), a.offsets, partial);
