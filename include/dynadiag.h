@@ -56,7 +56,8 @@ typedef enum { DD_F32 = 0, DD_BF16 = 1 } dd_dtype;
 typedef enum {
     DD_ALGO_AUTO = 0,
     DD_ALGO_VECTOR = 1, /* direct diagonal kernels on the vector ALUs: work ~ tokens*K*L   */
-    DD_ALGO_MATRIX = 2  /* W tiles rebuilt on chip and multiplied on the matrix cores       */
+    DD_ALGO_MATRIX = 2, /* W tiles rebuilt on chip and multiplied on the matrix cores       */
+    DD_ALGO_PREPARED = 3 /* as DD_ALGO_MATRIX, with the dense operands already built by dd_prepare */
 } dd_algo;
 
 typedef enum {
@@ -64,7 +65,8 @@ typedef enum {
     DD_OP_BWD_INPUT = 1,
     DD_OP_BWD_WEIGHT = 2,
     DD_OP_SELECT = 3,
-    DD_OP_SCALE_VALUES_BWD = 4 /* layer->K diagonals: scratch of dd_scale_values_bwd */
+    DD_OP_SCALE_VALUES_BWD = 4, /* layer->K diagonals: scratch of dd_scale_values_bwd */
+    DD_OP_PREPARE = 5           /* the block dd_prepare fills and DD_ALGO_PREPARED calls read */
 } dd_op;
 
 typedef struct {
@@ -92,6 +94,23 @@ size_t dd_workspace_bytes(int op, const dd_layer *layer, int32_t batch);
  */
 dd_status dd_fwd(const dd_layer *layer, const void *X, const int32_t *offsets, const void *values,
                  void *Y, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Builds once what dd_fwd and dd_bwd_input would otherwise rebuild on every call of the matrix-core path:
+ * the K diagonals of (offsets, values) laid out as the two dense bf16 operands (W_K for the forward
+ * product, its transpose for the backward one; Sec. 3.1 Eq. 1-3, Appendix A).  Meant for weights that
+ * serve several products: inference, where they never change, and training, where forward and backward
+ * of one step share them.
+ *   prepared: dd_workspace_bytes(DD_OP_PREPARE, layer, 0) bytes, 256-byte aligned, owned by the caller and
+ *   left alone by every other call; valid until offsets or values change.
+ * Afterwards dd_fwd / dd_bwd_input take layer->algo = DD_ALGO_PREPARED with ws = prepared (their offsets
+ * and values arguments are then not read).  dd_bwd_weight treats DD_ALGO_PREPARED like DD_ALGO_MATRIX and
+ * needs its own scratch.  layer->tokens is not used here.
+ * DD_ERR_UNSUPPORTED where DD_ALGO_MATRIX would be (dtype other than bf16, feature counts that are not
+ * multiples of 128).
+ */
+dd_status dd_prepare(const dd_layer *layer, const int32_t *offsets, const void *values, void *prepared,
+                     size_t prepared_bytes, void *hip_stream);
 
 /*
  * Backward product with respect to the input, dX = dY . W_K^T, over the same diagonals

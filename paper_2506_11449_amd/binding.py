@@ -12,10 +12,10 @@ import torch  # imported before the library so that both share one HIP runtime
 from .build import LIB_PATH
 
 DD_F32, DD_BF16 = 0, 1
-DD_ALGO_AUTO, DD_ALGO_VECTOR, DD_ALGO_MATRIX = 0, 1, 2
-DD_OP_FWD, DD_OP_BWD_INPUT, DD_OP_BWD_WEIGHT, DD_OP_SELECT, DD_OP_SCALE_VALUES_BWD = 0, 1, 2, 3, 4
+DD_ALGO_AUTO, DD_ALGO_VECTOR, DD_ALGO_MATRIX, DD_ALGO_PREPARED = 0, 1, 2, 3
+DD_OP_FWD, DD_OP_BWD_INPUT, DD_OP_BWD_WEIGHT, DD_OP_SELECT, DD_OP_SCALE_VALUES_BWD, DD_OP_PREPARE = 0, 1, 2, 3, 4, 5
 
-EXPORTS = ("dd_workspace_bytes", "dd_fwd", "dd_bwd_input", "dd_bwd_weight", "dd_select_diagonals",
+EXPORTS = ("dd_workspace_bytes", "dd_fwd", "dd_prepare", "dd_bwd_input", "dd_bwd_weight", "dd_select_diagonals",
            "dd_soft_topk", "dd_soft_topk_bwd", "dd_scale_values", "dd_scale_values_bwd", "dd_status_string")
 
 
@@ -46,6 +46,7 @@ def load_library():
     lib.dd_workspace_bytes.argtypes = [ctypes.c_int, lp, i32]
     lib.dd_workspace_bytes.restype = sz
     lib.dd_fwd.argtypes = [lp, vp, vp, vp, vp, vp, sz, vp]
+    lib.dd_prepare.argtypes = [lp, vp, vp, vp, sz, vp]
     lib.dd_bwd_input.argtypes = [lp, vp, vp, vp, vp, vp, sz, vp]
     lib.dd_bwd_weight.argtypes = [lp, vp, vp, vp, vp, vp, sz, vp]
     lib.dd_select_diagonals.argtypes = [i32, i32, i32, vp, vp, vp, sz, vp]
@@ -54,7 +55,7 @@ def load_library():
     lib.dd_soft_topk_bwd.argtypes = [i32, i32, i32, f32, vp, vp, vp, vp]
     lib.dd_scale_values.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp]
     lib.dd_scale_values_bwd.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
-    for name in ("dd_fwd", "dd_bwd_input", "dd_bwd_weight", "dd_select_diagonals", "dd_soft_topk",
+    for name in ("dd_fwd", "dd_prepare", "dd_bwd_input", "dd_bwd_weight", "dd_select_diagonals", "dd_soft_topk",
                  "dd_soft_topk_bwd", "dd_scale_values", "dd_scale_values_bwd"):
         getattr(lib, name).restype = ctypes.c_int
     lib.dd_status_string.argtypes = [ctypes.c_int]
@@ -135,38 +136,65 @@ def _ws_for(need, device, ws):
     return _ptr(buf), n
 
 
-def dd_fwd(X, offsets, values, out_features, Y=None, algo=DD_ALGO_AUTO, ws=None, stream=None):
-    """Y = X . W_K.  X [T x M], offsets int32 [K], values [K x min(M,N)] -> Y [T x N]."""
-    T, M = X.shape
-    N = int(out_features)
-    K = offsets.shape[0]
-    _, ref, need = _plan(DD_OP_FWD, T, M, N, K, X.dtype, algo)
-    _dev(X, X.dtype, (T, M), "X")
-    _dev(offsets, torch.int32, (K,), "offsets")
-    _dev(values, X.dtype, (K, min(M, N)), "values")
-    if Y is None:
-        Y = torch.empty((T, N), dtype=X.dtype, device=X.device)
-    _dev(Y, X.dtype, (T, N), "Y")
-    wp, wn = _ws_for(need, X.device, ws)
-    _check(_lib.dd_fwd(ref, _ptr(X), _ptr(offsets), _ptr(values), _ptr(Y), wp, wn, _stream(stream)))
-    return Y
+class Prepared:
+    """The block dd_prepare fills for one set of (offsets, values): the dense operands of dd_fwd / dd_bwd_input."""
+
+    def __init__(self, buf, in_features, out_features, K, dtype):
+        self.buf, self.in_features, self.out_features, self.K, self.dtype = buf, in_features, out_features, K, dtype
 
 
-def dd_bwd_input(dY, offsets, values, in_features, dX=None, algo=DD_ALGO_AUTO, ws=None, stream=None):
-    """dX = dY . W_K^T.  dY [T x N] -> dX [T x M]."""
-    T, N = dY.shape
-    M = int(in_features)
-    K = offsets.shape[0]
-    _, ref, need = _plan(DD_OP_BWD_INPUT, T, M, N, K, dY.dtype, algo)
-    _dev(dY, dY.dtype, (T, N), "dY")
+def dd_prepare(offsets, values, in_features, out_features, prepared=None, stream=None):
+    """Builds the dense operands of the matrix-core path once; pass the result as `prepared=` to dd_fwd / dd_bwd_input."""
+    M, N, K = int(in_features), int(out_features), offsets.shape[0]
+    _, ref, need = _plan(DD_OP_PREPARE, 0, M, N, K, values.dtype, DD_ALGO_PREPARED)
     _dev(offsets, torch.int32, (K,), "offsets")
-    _dev(values, dY.dtype, (K, min(M, N)), "values")
-    if dX is None:
-        dX = torch.empty((T, M), dtype=dY.dtype, device=dY.device)
-    _dev(dX, dY.dtype, (T, M), "dX")
-    wp, wn = _ws_for(need, dY.device, ws)
-    _check(_lib.dd_bwd_input(ref, _ptr(dY), _ptr(offsets), _ptr(values), _ptr(dX), wp, wn, _stream(stream)))
-    return dX
+    _dev(values, values.dtype, (K, min(M, N)), "values")
+    if prepared is None:
+        prepared = Prepared(torch.empty(max(need, 1), dtype=torch.uint8, device=values.device), M, N, K, values.dtype)
+    if (prepared.in_features, prepared.out_features, prepared.K, prepared.dtype) != (M, N, K, values.dtype):
+        raise ValueError("prepared block belongs to another layer")
+    _check(load_library().dd_prepare(ref, _ptr(offsets), _ptr(values), _ptr(prepared.buf), prepared.buf.numel(), _stream(stream)))
+    return prepared
+
+
+def _product(fn, op, src, offsets, values, n_src, n_dst, M, N, dst, algo, ws, stream, prepared, names):
+    T = src.shape[0]
+    if prepared is not None:
+        if (prepared.in_features, prepared.out_features, prepared.dtype) != (M, N, src.dtype):
+            raise ValueError("prepared block belongs to another layer")
+        algo, K = DD_ALGO_PREPARED, prepared.K
+    else:
+        K = offsets.shape[0]
+        _dev(offsets, torch.int32, (K,), "offsets")
+        _dev(values, src.dtype, (K, min(M, N)), "values")
+    _, ref, need = _plan(op, T, M, N, K, src.dtype, algo)
+    _dev(src, src.dtype, (T, n_src), names[0])
+    if dst is None:
+        dst = torch.empty((T, n_dst), dtype=src.dtype, device=src.device)
+    _dev(dst, src.dtype, (T, n_dst), names[1])
+    if prepared is not None:
+        wp, wn = _ptr(prepared.buf), prepared.buf.numel()
+        _check(fn(ref, _ptr(src), None, None, _ptr(dst), wp, wn, _stream(stream)))
+    else:
+        wp, wn = _ws_for(need, src.device, ws)
+        _check(fn(ref, _ptr(src), _ptr(offsets), _ptr(values), _ptr(dst), wp, wn, _stream(stream)))
+    return dst
+
+
+def dd_fwd(X, offsets, values, out_features, Y=None, algo=DD_ALGO_AUTO, ws=None, stream=None, prepared=None):
+    """Y = X . W_K.  X [T x M], offsets int32 [K], values [K x min(M,N)] -> Y [T x N].
+
+    With prepared= (from dd_prepare) offsets and values are not read and may be None."""
+    M, N = X.shape[1], int(out_features)
+    return _product(load_library().dd_fwd, DD_OP_FWD, X, offsets, values, M, N, M, N, Y, algo, ws, stream, prepared,
+                    ("X", "Y"))
+
+
+def dd_bwd_input(dY, offsets, values, in_features, dX=None, algo=DD_ALGO_AUTO, ws=None, stream=None, prepared=None):
+    """dX = dY . W_K^T.  dY [T x N] -> dX [T x M].  prepared= as for dd_fwd."""
+    M, N = int(in_features), dY.shape[1]
+    return _product(load_library().dd_bwd_input, DD_OP_BWD_INPUT, dY, offsets, values, N, M, M, N, dX, algo, ws, stream,
+                    prepared, ("dY", "dX"))
 
 
 def dd_bwd_weight(X, dY, offsets, dValues=None, algo=DD_ALGO_AUTO, ws=None, stream=None):

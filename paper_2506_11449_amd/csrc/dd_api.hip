@@ -20,7 +20,9 @@ dd_status check_layer(const dd_layer *l, Shape *s)
     if (!l) return DD_ERR_INVALID_ARG;
     if (l->tokens < 0 || l->in_features < 1 || l->out_features < 1 || l->K < 1) return DD_ERR_INVALID_ARG;
     if (l->dtype != DD_F32 && l->dtype != DD_BF16) return DD_ERR_INVALID_ARG;
-    if (l->algo != DD_ALGO_AUTO && l->algo != DD_ALGO_VECTOR && l->algo != DD_ALGO_MATRIX) return DD_ERR_INVALID_ARG;
+    if (l->algo != DD_ALGO_AUTO && l->algo != DD_ALGO_VECTOR && l->algo != DD_ALGO_MATRIX &&
+        l->algo != DD_ALGO_PREPARED)
+        return DD_ERR_INVALID_ARG;
     const int D = l->in_features > l->out_features ? l->in_features : l->out_features;
     const int L = l->in_features < l->out_features ? l->in_features : l->out_features;
     if (l->K > D) return DD_ERR_INVALID_ARG;
@@ -50,27 +52,32 @@ bool wants_matrix(const dd_layer *l, const Shape &s)
 {
     if (l->algo == DD_ALGO_VECTOR) return false;
     if (!dd::product_matrix_supported(l->tokens, s.D, s.L, l->dtype == DD_BF16)) return false;
-    return l->algo == DD_ALGO_MATRIX || int64_t(l->K) * 48 >= s.D;
+    return l->algo == DD_ALGO_MATRIX || l->algo == DD_ALGO_PREPARED || int64_t(l->K) * 48 >= s.D;
 }
+
+// the block dd_prepare fills: the operand of the forward product, then the one of the backward-input product
+size_t prepared_bytes(const Shape &s) { return 2 * dd::product_matrix_ws_bytes(s.D, s.L); }
 
 bool wants_matrix_wgrad(const dd_layer *l, const Shape &s)
 {
     if (l->algo == DD_ALGO_VECTOR) return false;
     if (!dd::weight_grad_matrix_supported(l->tokens, s.D, s.L, l->dtype == DD_BF16)) return false;
-    return l->algo == DD_ALGO_MATRIX || int64_t(l->K) * 48 >= s.D;
+    return l->algo == DD_ALGO_MATRIX || l->algo == DD_ALGO_PREPARED || int64_t(l->K) * 48 >= s.D;
 }
 
 dd_status product(const dd_layer *l, const Shape &s, bool transposed, const void *src, const int32_t *offsets,
                   const void *values, void *dst, void *ws, size_t ws_bytes, void *stream)
 {
-    if (!offsets || !values) return DD_ERR_INVALID_ARG;
+    const bool prepared = l->algo == DD_ALGO_PREPARED;
+    if (!prepared && (!offsets || !values)) return DD_ERR_INVALID_ARG;
     if (l->tokens > 0 && (!src || !dst)) return DD_ERR_INVALID_ARG;
+    bool matrix = wants_matrix(l, s);
+    if (prepared && !matrix) return DD_ERR_UNSUPPORTED;
     const size_t need = dd_workspace_bytes(transposed ? DD_OP_BWD_INPUT : DD_OP_FWD, l, 0);
     if (dd_status st = check_ws(ws, ws_bytes, need)) return st;
     if (l->tokens == 0) return DD_OK;
-    bool matrix = wants_matrix(l, s);
     if (matrix && !(aligned16(src) && aligned16(dst))) matrix = false;  // 16-byte vector accesses
-    if (l->algo == DD_ALGO_MATRIX && !matrix) return DD_ERR_UNSUPPORTED;
+    if ((l->algo == DD_ALGO_MATRIX || prepared) && !matrix) return DD_ERR_UNSUPPORTED;
     dd::ProductArgs a;
     a.T = l->tokens;
     a.D = s.D;
@@ -84,6 +91,10 @@ dd_status product(const dd_layer *l, const Shape &s, bool transposed, const void
     a.values = values;
     a.dst = dst;
     a.ws = ws;
+    if (prepared) {
+        a.prepared = true;
+        if (transposed) a.ws = static_cast<unsigned char *>(ws) + dd::product_matrix_ws_bytes(s.D, s.L);
+    }
     const hipError_t e = matrix ? dd::launch_product_matrix(a, static_cast<hipStream_t>(stream))
                                 : dd::launch_product_vector(a, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? DD_OK : DD_ERR_HIP;
@@ -108,7 +119,10 @@ size_t dd_workspace_bytes(int op, const dd_layer *layer, int32_t batch)
     switch (op) {
     case DD_OP_FWD:
     case DD_OP_BWD_INPUT:
+        if (layer->algo == DD_ALGO_PREPARED) return wants_matrix(layer, s) ? prepared_bytes(s) : 0;
         return wants_matrix(layer, s) ? dd::product_matrix_ws_bytes(s.D, s.L) : 0;
+    case DD_OP_PREPARE:
+        return dd::product_matrix_supported(1, s.D, s.L, layer->dtype == DD_BF16) ? prepared_bytes(s) : 0;
     case DD_OP_BWD_WEIGHT:
         return wants_matrix_wgrad(layer, s) ? dd::weight_grad_matrix_ws_bytes(layer->tokens, s.D, s.L, layer->K)
                                             : dd::weight_grad_vector_ws_bytes(layer->tokens, s.D, s.L, layer->K,
@@ -124,6 +138,23 @@ dd_status dd_fwd(const dd_layer *layer, const void *X, const int32_t *offsets, c
     Shape s;
     if (dd_status st = check_layer(layer, &s)) return st;
     return product(layer, s, false, X, offsets, values, Y, ws, ws_bytes, hip_stream);
+}
+
+dd_status dd_prepare(const dd_layer *layer, const int32_t *offsets, const void *values, void *prepared,
+                     size_t prepared_bytes_given, void *hip_stream)
+{
+    Shape s;
+    if (dd_status st = check_layer(layer, &s)) return st;
+    if (!offsets || !values) return DD_ERR_INVALID_ARG;
+    if (layer->algo == DD_ALGO_VECTOR) return DD_ERR_UNSUPPORTED;
+    if (!dd::product_matrix_supported(1, s.D, s.L, layer->dtype == DD_BF16)) return DD_ERR_UNSUPPORTED;
+    if (dd_status st = check_ws(prepared, prepared_bytes_given, prepared_bytes(s))) return st;
+    // the forward product is the masked gather when the layer expands (M <= N), else the plain gather
+    unsigned char *first = static_cast<unsigned char *>(prepared);
+    unsigned char *second = first + dd::product_matrix_ws_bytes(s.D, s.L);
+    const hipError_t e = dd::launch_prepare_matrix(s.D, s.L, layer->K, offsets, values, s.expanding ? first : second,
+                                                   s.expanding ? second : first, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? DD_OK : DD_ERR_HIP;
 }
 
 dd_status dd_bwd_input(const dd_layer *layer, const void *dY, const int32_t *offsets, const void *values, void *dX,

@@ -56,18 +56,23 @@ __device__ __forceinline__ size_t fragment_index(int j, int i, int KD)
 
 // ---------------------------------------------------------------------------------------------
 // Step 1: dense operand from the diagonals, one workgroup per output column r of the product.
-//   long_major = 1:  row r = q in [0, D), KD = L:  w[p] = sum_{k: (q - o_k) mod D = p < L} v_k[p]
-//   long_major = 0:  row r = p in [0, L), KD = D:  w[q] = sum_{k: (p + o_k) mod D = q} v_k[p]
-// The row is summed in fp32 in LDS (repeated offsets add, Eq. 3) and rounded to bf16 once.
+//   masked gather:  row r = q in [0, D), KD = L:  w[p] = sum_{k: (q - o_k) mod D = p < L} v_k[p]
+//   gather:         row r = p in [0, L), KD = D:  w[q] = sum_{k: (p + o_k) mod D = q} v_k[p]
+// The first `masked_rows` workgroups build rows of the masked-gather operand, the others rows of the
+// gather operand (either count may be zero).  A row is summed in fp32 in LDS (repeated offsets add, Eq. 3)
+// and rounded to bf16 once.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void materialize_kernel(int D, int L, int K, int long_major,
+__global__ __launch_bounds__(256) void materialize_kernel(int D, int L, int K, int masked_rows,
                                                           const int *__restrict__ offsets,
                                                           const uint16_t *__restrict__ values,
-                                                          uint16_t *__restrict__ Wf)
+                                                          uint16_t *__restrict__ Wf_masked,
+                                                          uint16_t *__restrict__ Wf_gather)
 {
     extern __shared__ float row[];
-    const int r = blockIdx.x;
+    const bool long_major = int(blockIdx.x) < masked_rows;
+    const int r = long_major ? blockIdx.x : blockIdx.x - masked_rows;
     const int KD = long_major ? L : D;
+    uint16_t *Wf = long_major ? Wf_masked : Wf_gather;
     for (int c = threadIdx.x; c < KD; c += 256) row[c] = 0.f;
     __syncthreads();
     for (int k = threadIdx.x; k < K; k += 256) {
@@ -301,6 +306,15 @@ static hipError_t launch_mm(int T, int NC, int KD, const uint16_t *A, const uint
     return hipGetLastError();
 }
 
+hipError_t launch_prepare_matrix(int D, int L, int K, const int32_t *offsets, const void *values, void *masked_operand,
+                                 void *gather_operand, hipStream_t stream)
+{
+    hipLaunchKernelGGL(materialize_kernel, dim3(D + L), dim3(256), size_t(D) * sizeof(float), stream, D, L, K, D, offsets,
+                       static_cast<const uint16_t *>(values), static_cast<uint16_t *>(masked_operand),
+                       static_cast<uint16_t *>(gather_operand));
+    return hipGetLastError();
+}
+
 constexpr int kMmWaves = DD_MM_WAVES;
 
 // Largest tile whose workgroup count fills the 256 CUs in the fewest, fullest rounds.
@@ -326,10 +340,12 @@ hipError_t launch_product_matrix(const ProductArgs &a, hipStream_t stream)
     const int NC = a.masked ? a.D : a.L;
     const int KD = a.masked ? a.L : a.D;
     uint16_t *Wf = static_cast<uint16_t *>(a.ws);
-    hipLaunchKernelGGL(materialize_kernel, dim3(NC), dim3(256), size_t(KD) * sizeof(float), stream, a.D, a.L, a.K,
-                       a.masked ? 1 : 0, a.offsets, static_cast<const uint16_t *>(a.values), Wf);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (!a.prepared) {
+        hipLaunchKernelGGL(materialize_kernel, dim3(NC), dim3(256), size_t(KD) * sizeof(float), stream, a.D, a.L, a.K,
+                           a.masked ? NC : 0, a.offsets, static_cast<const uint16_t *>(a.values), Wf, Wf);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     const uint16_t *A = static_cast<const uint16_t *>(a.src);
     uint16_t *C = static_cast<uint16_t *>(a.dst);
     const int T = int(a.T);

@@ -85,6 +85,32 @@ def test_workspace_rules(lib):
     assert lib.dd_bwd_input(ctypes.byref(z), None, one, one, None, None, 0, None) == 0
 
 
+def test_prepare_rules(lib):
+    one = ctypes.c_void_p(256)
+    ok = _layer(T=100, M=768, N=3072, K=30, dtype=1, algo=binding.DD_ALGO_PREPARED)
+    need = lib.dd_workspace_bytes(binding.DD_OP_PREPARE, ctypes.byref(ok), 0)
+    assert need == 2 * 768 * 3072 * 2  # both dense operands, bf16
+    # the prepared calls want the whole block, whatever the density
+    assert lib.dd_workspace_bytes(binding.DD_OP_FWD, ctypes.byref(ok), 0) == need
+    assert lib.dd_workspace_bytes(binding.DD_OP_BWD_INPUT, ctypes.byref(ok), 0) == need
+    assert lib.dd_prepare(ctypes.byref(ok), None, one, one, need, None) == 1
+    assert lib.dd_prepare(ctypes.byref(ok), one, None, one, need, None) == 1
+    assert lib.dd_prepare(ctypes.byref(ok), one, one, None, need, None) == 3
+    assert lib.dd_prepare(ctypes.byref(ok), one, one, ctypes.c_void_p(512), need - 1, None) == 3
+    assert lib.dd_prepare(ctypes.byref(ok), one, one, ctypes.c_void_p(520), need, None) == 3
+    # shapes and types the matrix-core kernels do not cover
+    for bad in (_layer(M=768, N=768, K=8, dtype=0, algo=binding.DD_ALGO_PREPARED),
+                _layer(M=100, N=768, K=8, dtype=1, algo=binding.DD_ALGO_PREPARED),
+                _layer(M=768, N=768, K=8, dtype=1, algo=binding.DD_ALGO_VECTOR)):
+        assert lib.dd_workspace_bytes(binding.DD_OP_PREPARE, ctypes.byref(bad), 0) in (0, 2 * 768 * 768 * 2)
+        assert lib.dd_prepare(ctypes.byref(bad), one, one, ctypes.c_void_p(512), 1 << 30, None) == 2
+    unsupported = _layer(T=8, M=100, N=768, K=8, dtype=1, algo=binding.DD_ALGO_PREPARED)
+    assert lib.dd_fwd(ctypes.byref(unsupported), one, None, None, one, ctypes.c_void_p(512), 1 << 30, None) == 2
+    # a prepared product does not read offsets / values, but still needs its block
+    assert lib.dd_fwd(ctypes.byref(ok), one, None, None, one, None, 0, None) == 3
+    assert lib.dd_bwd_input(ctypes.byref(ok), one, None, None, one, ctypes.c_void_p(512), need - 1, None) == 3
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     X = torch.zeros(4, 8)

@@ -92,6 +92,48 @@ def test_small_cases_elementwise(M, N, K, T, dtype, algo):
     check_against_oracle(offsets, values, X, dY, dtype, ALGOS[algo])
 
 
+PREPARED = [(768, 768, 77, 300), (768, 3072, 307, 130), (3072, 768, 307, 130), (128, 128, 13, 1), (256, 128, 26, 161),
+            (128, 384, 40, 415), (1024, 1024, 51, 257), (384, 1152, 60, 333)]
+
+
+@pytest.mark.parametrize("M,N,K,T", PREPARED)
+def test_prepared_products(M, N, K, T):
+    """dd_prepare once, then forward and backward-input products that read neither offsets nor values:
+    against the oracle, bit-identical to the calls that rebuild the operands themselves, and still right
+    after the block has been refilled for other offsets (duplicates and a negative one among them)."""
+    offsets, values, X, dY = random_case(M, N, K, T, "bf16", seed=77 * M + N + K)
+    d_X, d_dY = to_dev(X, "bf16"), to_dev(dY, "bf16")
+    prepared = None
+    for round_ in range(2):
+        if round_ == 1:
+            offsets = offsets.copy()
+            offsets[0] = offsets[-1]
+            offsets[K // 2] = offsets[-1] - max(M, N)
+        d_off = torch.from_numpy(offsets).cuda()
+        d_val = to_dev(values, "bf16")
+        prepared = dd.dd_prepare(d_off, d_val, M, N, prepared=prepared)
+        Y = dd.dd_fwd(d_X, None, None, N, prepared=prepared)
+        dX = dd.dd_bwd_input(d_dY, None, None, M, prepared=prepared)
+        Y2 = dd.dd_fwd(d_X, d_off, d_val, N, algo=dd.DD_ALGO_MATRIX)
+        dX2 = dd.dd_bwd_input(d_dY, d_off, d_val, M, algo=dd.DD_ALGO_MATRIX)
+        dV = dd.dd_bwd_weight(d_X, d_dY, d_off, algo=dd.DD_ALGO_PREPARED)  # same kernels as DD_ALGO_MATRIX
+        torch.cuda.synchronize()
+        assert torch.equal(Y.view(torch.int16), Y2.view(torch.int16))
+        assert torch.equal(dX.view(torch.int16), dX2.view(torch.int16))
+        assert rel_err(to_host(Y), orc.fwd(X, offsets, values, N)) <= TOL["bf16"]
+        assert rel_err(to_host(dX), orc.bwd_input(dY, offsets, values, M)) <= TOL["bf16"]
+        assert rel_err(to_host(dV), orc.bwd_weight(X, dY, offsets)) <= TOL_DV
+
+
+def test_prepared_refuses_what_the_matrix_cores_do_not_cover():
+    off = torch.zeros(4, dtype=torch.int32, device="cuda")
+    for M, N, dtype in ((100, 768, torch.bfloat16), (768, 768, torch.float32)):
+        val = torch.zeros((4, min(M, N)), dtype=dtype, device="cuda")
+        with pytest.raises(dd.DynaDiagError) as e:
+            dd.dd_prepare(off, val, M, N)
+        assert e.value.status == 2
+
+
 @pytest.mark.parametrize("algo", ["vector", "matrix", "auto"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_tiny_config(dtype, algo):
