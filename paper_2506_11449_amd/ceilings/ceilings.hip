@@ -107,6 +107,40 @@ __global__ __launch_bounds__(256) void lds_kernel(unsigned *out, int iters)
     out[blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// Cache read bandwidth: every workgroup streams again and again over a region small enough to stay in the
+// L2 of its XCD (or, larger, in the memory-side cache); 16 bytes per lane, eight loads in flight per lane.
+// to_lds = 1 moves the data straight into LDS (global_load_lds_dwordx4) instead of into registers.
+template <int TO_LDS>
+__global__ __launch_bounds__(256) void cache_read_kernel(const u32x4 *src, u32x4 *dst, int region_pieces, int iters)
+{
+    extern __shared__ __align__(16) unsigned char stage[];
+    const int wave = threadIdx.x >> 6;
+    const unsigned base = __builtin_amdgcn_readfirstlane(
+        unsigned(reinterpret_cast<size_t>((__attribute__((address_space(3))) unsigned char *)stage)) + wave * 1024);
+    u32x4 acc = {0, 0, 0, 0};
+    int pos = int((size_t(blockIdx.x) * 977 * 256 + threadIdx.x) % size_t(region_pieces));
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (TO_LDS)
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base + u * 4096),
+                             "v"(src + pos)
+                             : "memory", "m0");
+            else
+                acc ^= src[pos];
+            pos += 256;
+            pos = pos >= region_pieces ? pos - region_pieces : pos;
+        }
+        if (TO_LDS) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    }
+    if (TO_LDS) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        acc = *reinterpret_cast<const u32x4 *>(stage + threadIdx.x * 16);
+    }
+    if (acc[0] == 0x12345678u) dst[threadIdx.x] = acc;
+}
+
 int main()
 {
     hipDeviceProp_t prop;
@@ -199,6 +233,30 @@ int main()
         const double by = double(blocks) * 256 * iters * 8 * 16.0;
         printf("ds_read_b128, %d waves per CU: %.1f TB/s = %.0f B/clk/CU at 2.4 GHz\n", wpc, by / ms / 1e9,
                by / (ms * 1e-3) / cus / 2.4e9);
+    }
+    {  // reads served by the L2 (1 MB region per workgroup stream), by the memory-side cache (16 MB, 64 MB)
+        const size_t bytes = size_t(64) << 20;
+        u32x4 *src;
+        CK(hipMalloc(&src, bytes));
+        CK(hipMemset(src, 1, bytes));
+        CK(hipFuncSetAttribute((const void *)cache_read_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, 32768));
+        const int iters = 400, wgs = 1024;
+        for (int region_kb : {1024, 16384, 65536})
+            for (int to_lds = 0; to_lds < 2; ++to_lds) {
+                const int pieces = region_kb * 1024 / 16;
+                for (int rep = 0; rep < 2; ++rep) {
+                    CK(hipEventRecord(e0));
+                    if (to_lds) cache_read_kernel<1><<<wgs, 256, 32768>>>(src, (u32x4 *)out, pieces, iters);
+                    else cache_read_kernel<0><<<wgs, 256, 32768>>>(src, (u32x4 *)out, pieces, iters);
+                    CK(hipEventRecord(e1));
+                    CK(hipEventSynchronize(e1));
+                }
+                CK(hipEventElapsedTime(&ms, e0, e1));
+                const double tb = double(wgs) * 256 * 16 * 8 * iters / 1e12;
+                printf("cached reads, region %5d KB, into %s: %.1f TB/s = %.0f B/clk/CU at 2.4 GHz\n", region_kb,
+                       to_lds ? "LDS      " : "registers", tb / (ms * 1e-3), tb * 1e12 / (ms * 1e-3) / cus / 2.4e9);
+            }
+        CK(hipFree(src));
     }
     return 0;
 }
