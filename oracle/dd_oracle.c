@@ -13,6 +13,9 @@
  *   - hard TopK choice of K of the D candidate diagonals                (Sec. 3.2, Eq. 4)
  *   - soft TopK weights, their derivative, and the scaling of the
  *     diagonals by them with its adjoint                                (Sec. 3.2, Eq. 4 and Eq. 5)
+ *   - the heuristic update of the active set (DiagHeur): magnitude of
+ *     each diagonal, drop the weakest, grow as many at random           (Appendix "Details of the
+ *                                                                        Heuristics-Based Method")
  *
  * Reading of the rectangular convention (the paper states it in two incompatible
  * ways; this is the one under which the K-from-sparsity footnote of Sec. 3.1, the
@@ -307,4 +310,62 @@ void ddo_scale_values_bwd(int K, int L, int D, const int32_t *offsets, const dou
         }
         dalpha_tilde[o] += dot;
     }
+}
+
+/* ---- DiagHeur: prune the diagonals of lowest magnitude, grow as many at random (Appendix, heuristics) ---- */
+
+/*
+ * Magnitude of a diagonal.  The appendix says "lowest magnitudes" without naming a norm; RigL, which it
+ * follows, ranks single weights by |w|, so the sum of |v_k[p]| over the diagonal is read (all diagonals
+ * have the same length, so sum and mean rank alike).
+ */
+void ddo_diag_magnitude(int K, int L, const double *values, double *magnitudes)
+{
+    for (int k = 0; k < K; ++k) {
+        double s = 0.0;
+        for (int p = 0; p < L; ++p) s += fabs(values[(int64_t)k * L + p]);
+        magnitudes[k] = s;
+    }
+}
+
+/*
+ * One update of the active set.  offsets [K]: the active diagonals, distinct modulo D.  Of them the
+ * n_drop with the lowest magnitude leave (order: larger magnitude first, equal magnitudes by lower offset,
+ * NaN lowest; the first K - n_drop stay).  Of the D - K candidates that were not active, the n_drop with
+ * the largest `random` score enter (same order, by candidate index); a diagonal that has just left is not
+ * a candidate, as in RigL.  new_offsets [K]: the new set, ascending.  source [K]: for each new diagonal the
+ * position in `offsets` whose values it keeps, or -1 if it was grown (RigL starts grown weights at zero).
+ * Returns 1 if the arguments do not allow the update (n_drop > K or n_drop > D - K), 2 on allocation failure.
+ */
+int ddo_diagheur_update(int D, int K, int n_drop, const int32_t *offsets, const float *magnitudes,
+                        const float *random, int32_t *new_offsets, int32_t *source)
+{
+    if (n_drop < 0 || n_drop > K || n_drop > D - K) return 1;
+    int32_t *slot = (int32_t *)malloc(sizeof(int32_t) * (size_t)D);
+    scored *act = (scored *)malloc(sizeof(scored) * (size_t)K);
+    scored *cand = (scored *)malloc(sizeof(scored) * (size_t)(D - K > 0 ? D - K : 1));
+    if (!slot || !act || !cand) { free(slot); free(act); free(cand); return 2; }
+    for (int i = 0; i < D; ++i) slot[i] = -1;
+    for (int k = 0; k < K; ++k) {
+        const int o = (int)((((int64_t)offsets[k] % D) + D) % D);
+        slot[o] = k;
+        act[k].score = magnitudes[k];
+        act[k].index = o;
+    }
+    qsort(act, (size_t)K, sizeof(scored), scored_cmp);
+    int n = 0;
+    for (int i = 0; i < K - n_drop; ++i) new_offsets[n++] = act[i].index;
+    int c = 0;
+    for (int i = 0; i < D; ++i)
+        if (slot[i] < 0) { cand[c].score = random[i]; cand[c].index = i; ++c; }
+    qsort(cand, (size_t)c, sizeof(scored), scored_cmp);
+    for (int i = 0; i < n_drop; ++i) new_offsets[n++] = cand[i].index;
+    qsort(new_offsets, (size_t)K, sizeof(int32_t), int32_cmp);
+    for (int j = 0; j < K; ++j) {
+        const int k = slot[new_offsets[j]];
+        /* a diagonal that has just left cannot come back in the same update, so slot >= 0 means kept */
+        source[j] = k;
+    }
+    free(slot); free(act); free(cand);
+    return 0;
 }

@@ -68,6 +68,11 @@ def _load():
         lib.ddo_scale_values_bwd.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, _c_int32_p, _c_double_p,
                                              _c_double_p, _c_double_p, _c_double_p, _c_double_p]
         lib.ddo_scale_values_bwd.restype = None
+        lib.ddo_diag_magnitude.argtypes = [ctypes.c_int, ctypes.c_int, _c_double_p, _c_double_p]
+        lib.ddo_diag_magnitude.restype = None
+        lib.ddo_diagheur_update.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, _c_int32_p, _c_float_p,
+                                            _c_float_p, _c_int32_p, _c_int32_p]
+        lib.ddo_diagheur_update.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -226,3 +231,32 @@ def scale_values_bwd(offsets, alpha_tilde, V, dValues):
     dalpha = np.empty(D, dtype=np.float64)
     _load().ddo_scale_values_bwd(K, L, D, _ip(offsets), _dp(alpha_tilde), _dp(V), _dp(dValues), _dp(dV), _dp(dalpha))
     return dV, dalpha
+
+
+def diag_magnitude(values):
+    """Sum of |v_k[p]| over each diagonal (the appendix on the heuristics-based method)."""
+    values = _f64(values)
+    K, L = values.shape
+    out = np.empty(K, dtype=np.float64)
+    _load().ddo_diag_magnitude(K, L, _dp(values), _dp(out))
+    return out
+
+
+def diagheur_update(D, offsets, magnitudes, random, n_drop):
+    """(new_offsets [K] ascending, source [K]): drop the n_drop weakest active diagonals, grow the n_drop
+    inactive candidates with the largest random score."""
+    offsets = _i32(offsets)
+    K = offsets.shape[0]
+    magnitudes = np.ascontiguousarray(np.asarray(magnitudes, dtype=np.float32))
+    random = np.ascontiguousarray(np.asarray(random, dtype=np.float32))
+    if magnitudes.shape != (K,) or random.shape != (D,):
+        raise ValueError("magnitudes must be [K], random [D]")
+    new_offsets = np.empty(K, dtype=np.int32)
+    source = np.empty(K, dtype=np.int32)
+    rc = _load().ddo_diagheur_update(int(D), K, int(n_drop), _ip(offsets), magnitudes.ctypes.data_as(_c_float_p),
+                                     random.ctypes.data_as(_c_float_p), _ip(new_offsets), _ip(source))
+    if rc == 1:
+        raise ValueError("n_drop must be in [0, min(K, D - K)]")
+    if rc:
+        raise MemoryError
+    return new_offsets, source

@@ -356,3 +356,83 @@ def test_scale_values_and_its_adjoint():
         e[i] = 1e-4
         fd = (loss(alpha + e) - loss(alpha - e)) / 2e-4
         assert abs(fd - dalpha[i]) <= 1e-8 * max(1.0, abs(fd))
+
+
+# ---- DiagHeur: drop the weakest diagonals, grow as many at random (appendix on the heuristics-based method) ----
+
+def test_diag_magnitude_is_the_sum_of_absolute_values():
+    rng = np.random.default_rng(5)
+    V = rng.standard_normal((7, 33))
+    np.testing.assert_allclose(orc.diag_magnitude(V), np.abs(V).sum(axis=1), rtol=1e-14)
+    # closed forms: sign does not matter, scaling is homogeneous, a zero diagonal has magnitude zero
+    np.testing.assert_allclose(orc.diag_magnitude(-3.0 * V), 3.0 * orc.diag_magnitude(V), rtol=1e-14)
+    assert orc.diag_magnitude(np.zeros((2, 5))).tolist() == [0.0, 0.0]
+    assert orc.diag_magnitude(np.array([[1.0, -2.0, 3.0], [0.0, 0.0, -0.5]])).tolist() == [6.0, 0.5]
+
+
+def test_diagheur_update_worked_example():
+    # active {1, 3, 6} with magnitudes {5, 1, 3}: offset 3 is the weakest and leaves; of the inactive
+    # candidates {0, 2, 4, 5, 7} number 7 carries the largest random score and enters
+    new, src = orc.diagheur_update(8, [1, 3, 6], [5.0, 1.0, 3.0], [0.1, 0.9, 0.8, 0.7, 0.6, 0.5, 0.4, 0.95], 1)
+    assert new.tolist() == [1, 6, 7] and src.tolist() == [0, 2, -1]
+    # unsorted input, two leave: the kept one is found wherever it stands
+    new, src = orc.diagheur_update(8, [6, 1, 3], [3.0, 5.0, 1.0], [0.1, 0.9, 0.8, 0.7, 0.6, 0.5, 0.4, 0.95], 2)
+    assert new.tolist() == [1, 2, 7] and src.tolist() == [1, -1, -1]
+    # nothing leaves: the same set, ascending, every diagonal keeps its values
+    new, src = orc.diagheur_update(8, [6, 1, 3], [3.0, 5.0, 1.0], np.zeros(8), 0)
+    assert new.tolist() == [1, 3, 6] and src.tolist() == [1, 2, 0]
+    # offsets are taken modulo D; equal magnitudes leave by higher offset first, equal scores enter by lower index
+    new, src = orc.diagheur_update(6, [-1, 8], [2.0, 2.0], np.zeros(6), 1)   # offsets 5 and 2
+    assert new.tolist() == [0, 2] and src.tolist() == [-1, 1]
+    for bad in (3, -1):
+        with pytest.raises(ValueError):
+            orc.diagheur_update(5, [0, 1, 2], [1.0, 1.0, 1.0], np.zeros(5), bad)  # only two candidates to grow
+
+
+def _diagheur_by_numpy(D, offsets, mags, rnd, n_drop):
+    """The same update written with numpy's stable lexsort: keys (NaN last, value descending, index ascending)."""
+    offsets = np.mod(np.asarray(offsets, dtype=np.int64), D)
+    K = len(offsets)
+
+    def order(values, index):
+        values = np.asarray(values, dtype=np.float32)
+        nan = np.isnan(values)
+        return np.lexsort((index, -np.where(nan, 0, values), nan))
+
+    kept = offsets[order(mags, offsets)[:K - n_drop]]
+    inactive = np.setdiff1d(np.arange(D), offsets)
+    grown = inactive[order(np.asarray(rnd)[inactive], inactive)[:n_drop]]
+    new = np.sort(np.concatenate([kept, grown]))
+    slot = {int(o): k for k, o in enumerate(offsets)}
+    return new, np.array([slot[int(o)] if int(o) in set(kept.tolist()) else -1 for o in new])
+
+
+@pytest.mark.parametrize("D,K,n_drop,seed", [(16, 5, 2, 0), (64, 8, 8, 1), (64, 50, 14, 2), (768, 77, 23, 3),
+                                             (100, 100, 0, 4), (33, 1, 1, 5), (257, 128, 64, 6)])
+def test_diagheur_update_against_numpy_and_invariants(D, K, n_drop, seed):
+    rng = np.random.default_rng(seed)
+    offsets = rng.permutation(D)[:K].astype(np.int32)
+    # few distinct values so that ties occur, some NaN, signed zeros
+    mags = rng.integers(0, 4, K).astype(np.float32)
+    rnd = (rng.integers(0, 5, D) / 4).astype(np.float32)
+    if K > 3:
+        mags[1] = np.nan
+    if D > 10:
+        rnd[[2, 7]] = np.nan
+        rnd[5] = -0.0
+    new, src = orc.diagheur_update(D, offsets, mags, rnd, n_drop)
+    ref_new, ref_src = _diagheur_by_numpy(D, offsets, mags, rnd, n_drop)
+    assert new.tolist() == ref_new.tolist() and src.tolist() == ref_src.tolist()
+    # invariants: K distinct diagonals, ascending; the kept ones were active and keep their own values,
+    # the grown ones were not active; as many enter as leave
+    assert len(set(new.tolist())) == K and np.all(np.diff(new) > 0)
+    old = set(offsets.tolist())
+    assert sum(o not in old for o in new.tolist()) == n_drop == int(np.sum(src < 0))
+    for o, k in zip(new.tolist(), src.tolist()):
+        assert (k >= 0 and offsets[k] == o) or (k < 0 and o not in old)
+    # no dropped diagonal outranks a kept one
+    key = lambda m: -np.inf if np.isnan(m) else m
+    kept_slots = [k for k in src.tolist() if k >= 0]
+    dropped = [k for k in range(K) if k not in kept_slots]
+    if kept_slots and dropped:
+        assert max(key(mags[k]) for k in dropped) <= min(key(mags[k]) for k in kept_slots)
