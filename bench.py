@@ -251,6 +251,14 @@ def main():
                                              S, n, 5),
             "dd_soft_topk_bwd": time_loop(torch, lambda s: dd.dd_soft_topk_bwd(d_scores, K, 1.0, at), S, n, 5)}
     breakdown["soft_topk_path_us"] = {k: v * 1e3 for k, v in soft.items()}
+    # the heuristic update of the active set (appendix on the heuristics-based method), also outside the step
+    d_rand = torch.rand(D, device="cuda")
+    mag = dd.dd_diag_magnitude(d_val)
+    n_drop = max(1, (3 * K) // 10)  # RigL's initial drop fraction
+    heur = {"dd_diag_magnitude": time_loop(torch, lambda s: dd.dd_diag_magnitude(d_val, magnitudes=mag), S, n, 5),
+            "dd_diagheur_update": time_loop(torch, lambda s: dd.dd_diagheur_update(D, d_off[0], mag, d_rand, n_drop,
+                                                                                   ws=ws), S, n, 5)}
+    breakdown["diagheur_path_us"] = {k: v * 1e3 for k, v in heur.items()}
 
     if not args.no_dense:
         # dense bf16 GEMMs of the same shape (hipBLASLt / rocBLAS via torch.matmul), same rotation

@@ -66,7 +66,8 @@ typedef enum {
     DD_OP_BWD_WEIGHT = 2,
     DD_OP_SELECT = 3,
     DD_OP_SCALE_VALUES_BWD = 4, /* layer->K diagonals: scratch of dd_scale_values_bwd */
-    DD_OP_PREPARE = 5           /* the block dd_prepare fills and DD_ALGO_PREPARED calls read */
+    DD_OP_PREPARE = 5,          /* the block dd_prepare fills and DD_ALGO_PREPARED calls read */
+    DD_OP_DIAGHEUR = 6          /* layer->in_features candidates, layer->K diagonals: scratch of dd_diagheur_update */
 } dd_op;
 
 typedef struct {
@@ -178,6 +179,33 @@ dd_status dd_scale_values(int32_t K, int32_t L, int32_t D, int32_t dtype, const 
 dd_status dd_scale_values_bwd(int32_t K, int32_t L, int32_t D, int32_t dtype, const int32_t *offsets,
                               const float *alpha_tilde, const void *V, const float *dValues, float *dV,
                               float *d_alpha_tilde, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Magnitude of each diagonal, the quantity the heuristic variant of the method (DiagHeur, appendix "Details
+ * of the Heuristics-Based Method") ranks diagonals by.  The appendix names no norm; as in RigL, which it
+ * follows, absolute values are summed:  magnitudes[k] = sum_p |values[k][p]|   (fp32, fixed summation order).
+ *   values [K x L] of `dtype` in, magnitudes [K] fp32 out.
+ */
+dd_status dd_diag_magnitude(int32_t K, int32_t L, int32_t dtype, const void *values, float *magnitudes,
+                            void *hip_stream);
+
+/*
+ * One DiagHeur update of the active set: the n_drop active diagonals of lowest magnitude leave and the n_drop
+ * candidates with the largest `random` score among those that were not active enter (a diagonal that has just
+ * left cannot return in the same update).  Order in both choices: larger first, equal values by lower offset,
+ * NaN lowest.  The caller draws the random scores, so the update is a pure function of its arguments.
+ *   offsets     [K] int32  in   the active diagonals, distinct modulo D (as dd_select_diagonals emits them)
+ *   magnitudes  [K] fp32   in   non-negative, +inf or NaN (as dd_diag_magnitude emits them)
+ *   random      [D] fp32   in   finite or NaN
+ *   new_offsets [K] int32  out  the new active set, ascending
+ *   source      [K] int32  out  for new diagonal j the position in `offsets` whose values it keeps, or -1
+ *                               for a grown one (RigL starts grown weights at zero; that is the caller's move)
+ * DD_ERR_INVALID_ARG unless 0 <= n_drop <= min(K, D - K).  DD_ERR_UNSUPPORTED if D > 65536.
+ * ws: dd_workspace_bytes(DD_OP_DIAGHEUR, layer with in_features = D and K set, 0) bytes.
+ */
+dd_status dd_diagheur_update(int32_t D, int32_t K, int32_t n_drop, const int32_t *offsets, const float *magnitudes,
+                             const float *random, int32_t *new_offsets, int32_t *source, void *ws, size_t ws_bytes,
+                             void *hip_stream);
 
 const char *dd_status_string(dd_status status);
 

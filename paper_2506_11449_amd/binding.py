@@ -14,9 +14,11 @@ from .build import LIB_PATH
 DD_F32, DD_BF16 = 0, 1
 DD_ALGO_AUTO, DD_ALGO_VECTOR, DD_ALGO_MATRIX, DD_ALGO_PREPARED = 0, 1, 2, 3
 DD_OP_FWD, DD_OP_BWD_INPUT, DD_OP_BWD_WEIGHT, DD_OP_SELECT, DD_OP_SCALE_VALUES_BWD, DD_OP_PREPARE = 0, 1, 2, 3, 4, 5
+DD_OP_DIAGHEUR = 6
 
 EXPORTS = ("dd_workspace_bytes", "dd_fwd", "dd_prepare", "dd_bwd_input", "dd_bwd_weight", "dd_select_diagonals",
-           "dd_soft_topk", "dd_soft_topk_bwd", "dd_scale_values", "dd_scale_values_bwd", "dd_status_string")
+           "dd_soft_topk", "dd_soft_topk_bwd", "dd_scale_values", "dd_scale_values_bwd", "dd_diag_magnitude",
+           "dd_diagheur_update", "dd_status_string")
 
 
 class DynaDiagError(RuntimeError):
@@ -55,7 +57,9 @@ def load_library():
     lib.dd_soft_topk_bwd.argtypes = [i32, i32, i32, f32, vp, vp, vp, vp]
     lib.dd_scale_values.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp]
     lib.dd_scale_values_bwd.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
-    for name in ("dd_fwd", "dd_prepare", "dd_bwd_input", "dd_bwd_weight", "dd_select_diagonals", "dd_soft_topk",
+    lib.dd_diag_magnitude.argtypes = [i32, i32, i32, vp, vp, vp]
+    lib.dd_diagheur_update.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    for name in ("dd_diag_magnitude", "dd_diagheur_update", "dd_fwd", "dd_prepare", "dd_bwd_input", "dd_bwd_weight", "dd_select_diagonals", "dd_soft_topk",
                  "dd_soft_topk_bwd", "dd_scale_values", "dd_scale_values_bwd"):
         getattr(lib, name).restype = ctypes.c_int
     lib.dd_status_string.argtypes = [ctypes.c_int]
@@ -284,3 +288,36 @@ def dd_scale_values_bwd(offsets, alpha_tilde, V, dValues, ws=None, stream=None):
     _check(load_library().dd_scale_values_bwd(K, L, D, _DTYPES[V.dtype], _ptr(offsets), _ptr(alpha_tilde), _ptr(V),
                                               _ptr(dValues), _ptr(dV), _ptr(d_alpha), wp, wn, _stream(stream)))
     return dV, d_alpha
+
+
+def dd_diag_magnitude(values, magnitudes=None, stream=None):
+    """magnitudes[k] = sum_p |values[k][p]| (fp32) for values [K x L]."""
+    K, L = values.shape
+    _dev(values, values.dtype, (K, L), "values")
+    if magnitudes is None:
+        magnitudes = torch.empty(K, dtype=torch.float32, device=values.device)
+    _dev(magnitudes, torch.float32, (K,), "magnitudes")
+    _check(load_library().dd_diag_magnitude(K, L, _DTYPES[values.dtype], _ptr(values), _ptr(magnitudes),
+                                            _stream(stream)))
+    return magnitudes
+
+
+def dd_diagheur_update(D, offsets, magnitudes, random, n_drop, new_offsets=None, source=None, ws=None, stream=None):
+    """Drop the n_drop weakest active diagonals, grow the n_drop inactive candidates with the largest random score.
+
+    Returns (new_offsets [K] ascending, source [K]: position in `offsets` or -1 for a grown diagonal)."""
+    D, K = int(D), offsets.shape[0]
+    _dev(offsets, torch.int32, (K,), "offsets")
+    _dev(magnitudes, torch.float32, (K,), "magnitudes")
+    _dev(random, torch.float32, (D,), "random")
+    if new_offsets is None:
+        new_offsets = torch.empty(K, dtype=torch.int32, device=offsets.device)
+    if source is None:
+        source = torch.empty(K, dtype=torch.int32, device=offsets.device)
+    _dev(new_offsets, torch.int32, (K,), "new_offsets")
+    _dev(source, torch.int32, (K,), "source")
+    _, _, need = _plan(DD_OP_DIAGHEUR, 0, D, D, K, DD_F32, DD_ALGO_AUTO)
+    wp, wn = _ws_for(need, offsets.device, ws)
+    _check(load_library().dd_diagheur_update(D, K, int(n_drop), _ptr(offsets), _ptr(magnitudes), _ptr(random),
+                                             _ptr(new_offsets), _ptr(source), wp, wn, _stream(stream)))
+    return new_offsets, source

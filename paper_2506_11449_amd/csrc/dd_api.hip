@@ -110,6 +110,10 @@ size_t dd_workspace_bytes(int op, const dd_layer *layer, int32_t batch)
         if (!layer) return 0;
         return select_ws_bytes(batch, layer->in_features, layer->K);
     }
+    if (op == DD_OP_DIAGHEUR) {
+        if (!layer || layer->in_features < 1 || layer->K < 1 || layer->K > layer->in_features) return 0;
+        return dd::diagheur_ws_bytes(layer->in_features, layer->K);
+    }
     if (op == DD_OP_SCALE_VALUES_BWD) {
         if (!layer || layer->K < 1) return 0;
         return (size_t(layer->K) * sizeof(float) + kWsAlign - 1) / kWsAlign * kWsAlign;
@@ -254,6 +258,31 @@ dd_status dd_scale_values_bwd(int32_t K, int32_t L, int32_t D, int32_t dtype, co
     if (dd_status st = check_ws(ws, ws_bytes, need)) return st;
     return dd::launch_scale_values_bwd(K, L, D, dtype == DD_BF16, offsets, alpha_tilde, V, dValues, dV, d_alpha_tilde,
                                        static_cast<float *>(ws), static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? DD_OK
+               : DD_ERR_HIP;
+}
+
+dd_status dd_diag_magnitude(int32_t K, int32_t L, int32_t dtype, const void *values, float *magnitudes,
+                            void *hip_stream)
+{
+    if (K < 1 || L < 1 || (dtype != DD_F32 && dtype != DD_BF16)) return DD_ERR_INVALID_ARG;
+    if (!values || !magnitudes) return DD_ERR_INVALID_ARG;
+    return dd::launch_diag_magnitude(K, L, dtype == DD_BF16, values, magnitudes,
+                                     static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? DD_OK
+               : DD_ERR_HIP;
+}
+
+dd_status dd_diagheur_update(int32_t D, int32_t K, int32_t n_drop, const int32_t *offsets, const float *magnitudes,
+                             const float *random, int32_t *new_offsets, int32_t *source, void *ws, size_t ws_bytes,
+                             void *hip_stream)
+{
+    if (D < 1 || K < 1 || K > D || n_drop < 0 || n_drop > K || n_drop > D - K) return DD_ERR_INVALID_ARG;
+    if (D > 65536) return DD_ERR_UNSUPPORTED;
+    if (!offsets || !magnitudes || !random || !new_offsets || !source) return DD_ERR_INVALID_ARG;
+    if (dd_status st = check_ws(ws, ws_bytes, dd::diagheur_ws_bytes(D, K))) return st;
+    return dd::launch_diagheur_update(D, K, n_drop, offsets, magnitudes, random, new_offsets, source, ws,
+                                      static_cast<hipStream_t>(hip_stream)) == hipSuccess
                ? DD_OK
                : DD_ERR_HIP;
 }

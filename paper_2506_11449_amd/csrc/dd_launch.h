@@ -70,4 +70,10 @@ hipError_t launch_scale_values_bwd(int K, int L, int D, bool bf16, const int *of
                                    const void *V, const float *dValues, float *dV, float *dalpha, float *dots,
                                    hipStream_t stream);
 
+// DiagHeur: magnitude of each diagonal, and the update of the active set built on launch_select
+hipError_t launch_diag_magnitude(int K, int L, bool bf16, const void *values, float *magnitudes, hipStream_t stream);
+size_t diagheur_ws_bytes(int D, int K);
+hipError_t launch_diagheur_update(int D, int K, int n_drop, const int *offsets, const float *magnitudes,
+                                  const float *random, int *new_offsets, int *source, void *ws, hipStream_t stream);
+
 }  // namespace dd

@@ -111,6 +111,25 @@ def test_prepare_rules(lib):
     assert lib.dd_bwd_input(ctypes.byref(ok), one, None, None, one, ctypes.c_void_p(512), need - 1, None) == 3
 
 
+def test_diagheur_rules(lib):
+    one = ctypes.c_void_p(256)
+    l = _layer(M=768, N=768, K=77)
+    need = lib.dd_workspace_bytes(binding.DD_OP_DIAGHEUR, ctypes.byref(l), 0)
+    assert need == 2 * 768 * 4 + 512  # scores, table, kept offsets; each part rounded up to 256 bytes
+    args = (one, one, one, one, one, ctypes.c_void_p(512), need, None)
+    assert lib.dd_diagheur_update(768, 77, -1, *args) == 1
+    assert lib.dd_diagheur_update(768, 77, 78, *args) == 1           # more than are active
+    assert lib.dd_diagheur_update(100, 77, 24, *args) == 1           # more than there are candidates to grow
+    assert lib.dd_diagheur_update(768, 0, 0, *args) == 1
+    assert lib.dd_diagheur_update(1 << 20, 77, 3, *args) == 2
+    assert lib.dd_diagheur_update(768, 77, 7, None, one, one, one, one, ctypes.c_void_p(512), need, None) == 1
+    assert lib.dd_diagheur_update(768, 77, 7, one, one, one, one, one, None, 0, None) == 3
+    assert lib.dd_diagheur_update(768, 77, 7, one, one, one, one, one, ctypes.c_void_p(512), need - 1, None) == 3
+    assert lib.dd_diag_magnitude(0, 8, 0, one, one, None) == 1
+    assert lib.dd_diag_magnitude(4, 8, 5, one, one, None) == 1
+    assert lib.dd_diag_magnitude(4, 8, 0, None, one, None) == 1
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     X = torch.zeros(4, 8)
