@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--algo", default="auto", choices=["auto", "vector", "matrix"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--offset-bands", type=int, default=0,
+                    help="0: seeded uniform offsets (the benchmark); n > 0: the K diagonals in n runs of adjacent ones")
     ap.add_argument("--no-prepare", action="store_true", help="every product rebuilds its dense operand itself")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (a known-size reference for the "
@@ -107,6 +109,8 @@ def main():
     # set 0 holds the seeded inputs; the other sets are device-side copies (same values, other addresses)
     offsets, values, X, dY = synth.layer_inputs(layer, seed=2506)
     scores = synth.draw_scores(1, D, seed=2506)
+    if args.offset_bands > 0:  # the selection then returns exactly the clustered set
+        scores[0, synth.draw_offsets_clustered(D, K, args.offset_bands, seed=2506)] += 100.0
     S = max(1, args.sets)
     d_val = dev(values)
     d_scores = torch.from_numpy(scores).cuda()
@@ -284,6 +288,7 @@ def main():
                    else layer.name,
                    "step": ("dd_select_diagonals + dd_prepare + dd_fwd + dd_bwd_input + dd_bwd_weight" if use_prepare
                             else "dd_select_diagonals + dd_fwd + dd_bwd_input + dd_bwd_weight"),
+                   "offsets": "uniform" if args.offset_bands == 0 else f"{args.offset_bands} runs of adjacent diagonals",
                    "algo": args.algo, "buffer_sets": S, "tokens": T, "in_features": M, "out_features": N, "K": K},
         "roofline": roofline,
         "breakdown": breakdown,

@@ -29,6 +29,24 @@ def draw_offsets(D, K, seed, stream=0):
     return np.sort(perm).astype(np.int32)
 
 
+def draw_offsets_clustered(D, K, bands, seed, stream=0):
+    """K distinct offsets in `bands` runs of adjacent diagonals (run starts uniform, runs may wrap past D and
+    never overlap), ascending (int32): a stand-in for learned offsets that cluster, of which none exist here."""
+    rng = _rng(seed, 3, stream)
+    widths = np.full(bands, K // bands)
+    widths[:K % bands] += 1
+    gap_total = D - K
+    # distribute the free candidates over the gaps between consecutive runs (cyclically), then rotate
+    cuts = np.sort(rng.integers(0, gap_total + 1, bands - 1)) if bands > 1 else np.array([], dtype=np.int64)
+    gaps = np.diff(np.concatenate([[0], cuts, [gap_total]]))
+    start = int(rng.integers(0, D))
+    out = []
+    for w, g in zip(widths, gaps):
+        out.extend((start + i) % D for i in range(int(w)))
+        start += int(w) + int(g)
+    return np.sort(np.array(out, dtype=np.int64)).astype(np.int32)
+
+
 def draw_normal(shape, std, seed, stream):
     """fp32 N(0, std^2) samples."""
     return (_rng(seed, 2, stream).standard_normal(shape, dtype=np.float32) * np.float32(std)).astype(np.float32)

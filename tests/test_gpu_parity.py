@@ -135,6 +135,17 @@ def test_prepared_refuses_what_the_matrix_cores_do_not_cover():
 
 
 @pytest.mark.parametrize("algo", ["vector", "matrix", "auto"])
+@pytest.mark.parametrize("M,N,K,bands", [(768, 768, 77, 5), (768, 768, 77, 1), (384, 1152, 115, 4), (1152, 384, 60, 7),
+                                         (100, 260, 31, 3)])
+def test_clustered_offsets(M, N, K, bands, algo):
+    """Runs of adjacent diagonals (the structure learned offsets are expected to have), some wrapping past D."""
+    offsets = synth.draw_offsets_clustered(max(M, N), K, bands, seed=M + N + bands)
+    for dtype in ("f32", "bf16"):
+        _, values, X, dY = random_case(M, N, K, 150, dtype, seed=K, offsets=offsets)
+        check_against_oracle(offsets, values, X, dY, dtype, ALGOS[algo])
+
+
+@pytest.mark.parametrize("algo", ["vector", "matrix", "auto"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_tiny_config(dtype, algo):
     layer = synth.WORKLOADS["tiny"][0]
