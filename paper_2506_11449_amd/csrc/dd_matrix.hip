@@ -278,6 +278,186 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
 }
 
 // ---------------------------------------------------------------------------------------------
+// Step 2 for products with more tiles than CUs: one workgroup per CU walks a list of tiles, and the
+// software pipeline of mm_kernel runs through from tile to tile: while the last k-slices of a tile are
+// multiplied, the first slices of the next tile are already on their way (where mm_kernel re-reads the
+// last slice to keep its loop uniform), so a tile costs its main loop and the copy-out of its result, not
+// another fill of the pipeline.  The result tile has an LDS buffer of its own beside the ring.
+// ---------------------------------------------------------------------------------------------
+template <int BM, int BN, int NW>
+__global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, int KD, int tiles_m, int tiles_n,
+                                                                  const uint16_t *__restrict__ A,
+                                                                  const uint16_t *__restrict__ Wf,
+                                                                  uint16_t *__restrict__ C)
+{
+    using Tl = MmTile<BM, BN, NW>;
+    constexpr int kMmThreads = Tl::THREADS;
+    constexpr int kSlots = 256 / kXcds;  // workgroups per XCD: one per CU
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char *c_buf = smem + kRing * Tl::X_BYTES;
+
+    // The tiles are cut into one contiguous run per XCD (column tiles innermost, so that tiles sharing a
+    // token block run on the same L2); workgroup `slot` of an XCD takes every kSlots-th tile of its run.
+    const int n_tiles = tiles_m * tiles_n;
+    const int per_xcd = (n_tiles + kXcds - 1) / kXcds;
+    const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+    const int run_begin = xcd * per_xcd, run_end = min(run_begin + per_xcd, n_tiles);
+    const int first = run_begin + slot;
+    if (first >= run_end) return;
+    const int n_mine = (run_end - first + kSlots - 1) / kSlots;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int KT = KD / kBK;  // even: feature counts are multiples of 128
+    const int total = n_mine * KT;  // k-slices of all my tiles, numbered through
+
+    int x_row[Tl::X_CHUNKS], x_col[Tl::X_CHUNKS], x_dst[Tl::X_CHUNKS];
+#pragma unroll
+    for (int n = 0; n < Tl::X_CHUNKS; ++n) {
+        const int idx = min(tid + kMmThreads * n, BM * kChunksPerRow - 1);  // a last partial round repeats the final piece
+        x_row[n] = idx / kChunksPerRow;
+        x_col[n] = (idx % kChunksPerRow) * 8;
+        x_dst[n] = x_row[n] * kRowBytes + swizzle(x_row[n], idx % kChunksPerRow) * 16;
+    }
+    int b_off[Tl::FB], b_sw[Tl::FB];
+#pragma unroll
+    for (int b = 0; b < Tl::FB; ++b) {
+        const int row = b * 32 + l32;
+        b_off[b] = row * kRowBytes;
+        b_sw[b] = swizzle_key(row);
+    }
+
+    f32x16 acc[Tl::FA][Tl::FB];
+#pragma unroll
+    for (int a = 0; a < Tl::FA; ++a)
+#pragma unroll
+        for (int b = 0; b < Tl::FB; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+    u32x4 xg0[Tl::X_CHUNKS], xg1[Tl::X_CHUNKS];
+    bf16x8 wf0[4][Tl::FA], wf1[4][Tl::FA];
+    bf16x8 xf0[Tl::FB], xf1[Tl::FB];
+
+    // slice g_ (clamped to the last one) -> its tile and its place in it
+#define DD_WHERE(g_)                                                                                    \
+    const int g_c = (g_) < total ? (g_) : total - 1;                                                    \
+    const int lin = first + (g_c / KT) * kSlots;                                                        \
+    const int kt_in = g_c % KT;                                                                         \
+    const int tm_of = lin / tiles_n, tn_of = lin % tiles_n;
+#define DD_LOAD_X(xg_, g_)                                                                              \
+    {                                                                                                   \
+        DD_WHERE(g_)                                                                                    \
+        (void)tn_of;                                                                                    \
+        _Pragma("unroll") for (int n = 0; n < Tl::X_CHUNKS; ++n) {                                      \
+            const int t = min(tm_of * BM + x_row[n], T - 1); /* rows past the end re-read the last token */ \
+            xg_[n] = *reinterpret_cast<const u32x4 *>(A + size_t(t) * KD + x_col[n] + kt_in * kBK);     \
+        }                                                                                               \
+    }
+#define DD_STORE_X(xg_, g_)                                                                             \
+    {                                                                                                   \
+        unsigned char *dstb = smem + ((g_) % kRing) * Tl::X_BYTES;                                      \
+        _Pragma("unroll") for (int n = 0; n < Tl::X_CHUNKS; ++n)                                        \
+            *reinterpret_cast<u32x4 *>(dstb + x_dst[n]) = xg_[n];                                       \
+    }
+#define DD_LOAD_W(wf_, g_)                                                                              \
+    {                                                                                                   \
+        DD_WHERE(g_)                                                                                    \
+        (void)tm_of;                                                                                    \
+        _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a) {                                            \
+            const uint16_t *w = Wf + (size_t((tn_of * BN + wave * Tl::WN) / 32 + a) * (KD / 16) * 64 + lane) * 8 + \
+                                size_t(kt_in) * 4 * 512;                                                \
+            _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                            \
+                wf_[ks][a] = *reinterpret_cast<const bf16x8 *>(w + ks * 512);                           \
+        }                                                                                               \
+    }
+#define DD_LOAD_XF(xf_, g_, ks_)                                                                        \
+    {                                                                                                   \
+        const unsigned char *srcb = smem + ((g_) % kRing) * Tl::X_BYTES;                                \
+        const int ch = (ks_) * 2 + half;                                                                \
+        _Pragma("unroll") for (int b = 0; b < Tl::FB; ++b)                                              \
+            xf_[b] = *reinterpret_cast<const bf16x8 *>(srcb + b_off[b] + ((ch ^ b_sw[b]) << 4));        \
+    }
+#define DD_MFMA(wf_, ks_, xf_)                                                                          \
+    _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a)                                                  \
+        _Pragma("unroll") for (int b = 0; b < Tl::FB; ++b)                                              \
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf_[ks_][a], xf_[b], acc[a][b], 0, 0, 0);
+#define DD_SLICE(g_, wf_cur_, wf_next_, xg_)                                                            \
+    DD_LOAD_W(wf_next_, (g_) + 1)                                                                       \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_LOAD_XF(xf1, g_, 1)                                                                              \
+    DD_MFMA(wf_cur_, 0, xf0)                                                                            \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_LOAD_XF(xf0, g_, 2)                                                                              \
+    DD_MFMA(wf_cur_, 1, xf1)                                                                            \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_LOAD_XF(xf1, g_, 3)                                                                              \
+    DD_MFMA(wf_cur_, 2, xf0)                                                                            \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_LOAD_XF(xf0, (g_) + 1, 0)                                                                        \
+    DD_MFMA(wf_cur_, 3, xf1)                                                                            \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    DD_STORE_X(xg_, (g_) + 2)                                                                           \
+    DD_LOAD_X(xg_, (g_) + 4)                                                                            \
+    __syncthreads();
+
+    DD_LOAD_X(xg0, 0)
+    DD_LOAD_X(xg1, 1)
+    DD_LOAD_W(wf0, 0)
+    DD_STORE_X(xg0, 0)
+    DD_STORE_X(xg1, 1)
+    DD_LOAD_X(xg0, 2)
+    DD_LOAD_X(xg1, 3)
+    __syncthreads();
+    DD_LOAD_XF(xf0, 0, 0)
+    int kt = 0, tile_lin = first;
+    for (int g = 0; g < total; g += 2) {
+        DD_SLICE(g, wf0, wf1, xg0)
+        DD_SLICE(g + 1, wf1, wf0, xg1)
+        kt += 2;
+        if (kt == KT) {  // uniform: the tile is complete
+            const int tm = tile_lin / tiles_n, tn = tile_lin % tiles_n;
+            // Accumulator i of lane l is output column 8*(i/4) + 4*(l/32) + i%4 of token l%32 inside its 32x32
+            // tile.  (The copy-out of the previous tile finished before the barriers of this tile's slices.)
+#pragma unroll
+            for (int a = 0; a < Tl::FA; ++a)
+#pragma unroll
+                for (int b = 0; b < Tl::FB; ++b)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        f32x4 v = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
+                        const bf16x4 h = __builtin_convertvector(v, bf16x4);
+                        const int t_local = b * 32 + l32;
+                        const int j_local = wave * Tl::WN + a * 32 + 8 * q + 4 * half;
+                        *reinterpret_cast<bf16x4 *>(c_buf + t_local * Tl::C_STRIDE + j_local * 2) = h;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) acc[a][b][4 * q + i] = 0.f;
+                    }
+            __syncthreads();
+            constexpr int ROW_CHUNKS = BN / 8;
+            for (int idx = tid; idx < BM * ROW_CHUNKS; idx += kMmThreads) {
+                const int row = idx / ROW_CHUNKS, ch = idx % ROW_CHUNKS;
+                const int t = tm * BM + row;
+                if (t < T)
+                    *reinterpret_cast<u32x4 *>(C + size_t(t) * NC + tn * BN + ch * 8) =
+                        *reinterpret_cast<const u32x4 *>(c_buf + row * Tl::C_STRIDE + ch * 16);
+            }
+            kt = 0;
+            tile_lin += kSlots;
+        }
+    }
+#undef DD_WHERE
+#undef DD_LOAD_X
+#undef DD_STORE_X
+#undef DD_LOAD_W
+#undef DD_LOAD_XF
+#undef DD_MFMA
+#undef DD_SLICE
+}
+
+// ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
 bool product_matrix_supported(int64_t T, int D, int L, bool bf16)
@@ -312,6 +492,26 @@ hipError_t launch_prepare_matrix(int D, int L, int K, const int32_t *offsets, co
     hipLaunchKernelGGL(materialize_kernel, dim3(D + L), dim3(256), size_t(D) * sizeof(float), stream, D, L, K, D, offsets,
                        static_cast<const uint16_t *>(values), static_cast<uint16_t *>(masked_operand),
                        static_cast<uint16_t *>(gather_operand));
+    return hipGetLastError();
+}
+
+template <int BM, int BN, int NW>
+static hipError_t launch_mm_persistent(int T, int NC, int KD, const uint16_t *A, const uint16_t *Wf, uint16_t *C,
+                                       hipStream_t stream)
+{
+    using Tl = MmTile<BM, BN, NW>;
+    constexpr int kLds = kRing * Tl::X_BYTES + Tl::C_BYTES;
+    static_assert(kLds <= 160 * 1024, "ring and result tile fit the LDS of a CU");
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&mm_persistent_kernel<BM, BN, NW>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int tiles_m = (T + BM - 1) / BM, tiles_n = NC / BN;
+    hipLaunchKernelGGL((mm_persistent_kernel<BM, BN, NW>), dim3(256), dim3(Tl::THREADS), kLds, stream, T, NC, KD,
+                       tiles_m, tiles_n, A, Wf, C);
     return hipGetLastError();
 }
 
@@ -353,6 +553,9 @@ hipError_t launch_product_matrix(const ProductArgs &a, hipStream_t stream)
     return launch_mm<DD_MM_FORCE>(T, NC, KD, A, Wf, C, stream);  // tuning builds only
 #endif
     if (NC % 256 == 0) {
+        // more tiles than CUs: one workgroup per CU walks its tiles with the pipeline kept running
+        const int64_t tiles160 = ((a.T + 159) / 160) * (NC / 256);
+        if (tiles160 > 256) return launch_mm_persistent<160, 256, kMmWaves>(T, NC, KD, A, Wf, C, stream);
         switch (pick_tile(a.T, NC)) {
         case 192: return launch_mm<192, 256, kMmWaves>(T, NC, KD, A, Wf, C, stream);
         case 160: return launch_mm<160, 256, kMmWaves>(T, NC, KD, A, Wf, C, stream);

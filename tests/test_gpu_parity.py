@@ -134,6 +134,21 @@ def test_prepared_refuses_what_the_matrix_cores_do_not_cover():
         assert e.value.status == 2
 
 
+@pytest.mark.parametrize("M,N,K,T", [(128, 8192, 100, 1300), (8192, 128, 100, 1300), (512, 2048, 60, 5300),
+                                     (2048, 512, 60, 5301)])
+def test_more_tiles_than_cus(M, N, K, T):
+    """Products whose result has more than 256 tiles of 160 x 256: each workgroup walks several tiles with the
+    pipeline running through (two k-slices per tile in the widest cases, a ragged last token tile)."""
+    offsets, values, X, dY = random_case(M, N, K, T, "bf16", seed=M + N + T)
+    check_against_oracle(offsets, values, X, dY, "bf16", ALGOS["matrix"])
+    d_off, d_val = torch.from_numpy(offsets).cuda(), to_dev(values, "bf16")
+    prepared = dd.dd_prepare(d_off, d_val, M, N)
+    Y = dd.dd_fwd(to_dev(X, "bf16"), None, None, N, prepared=prepared)
+    dX = dd.dd_bwd_input(to_dev(dY, "bf16"), None, None, M, prepared=prepared)
+    assert rel_err(to_host(Y), orc.fwd(X, offsets, values, N)) <= TOL["bf16"]
+    assert rel_err(to_host(dX), orc.bwd_input(dY, offsets, values, M)) <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("algo", ["vector", "matrix", "auto"])
 @pytest.mark.parametrize("M,N,K,bands", [(768, 768, 77, 5), (768, 768, 77, 1), (384, 1152, 115, 4), (1152, 384, 60, 7),
                                          (100, 260, 31, 3)])
