@@ -552,9 +552,9 @@ hipError_t launch_product_matrix(const ProductArgs &a, hipStream_t stream)
 #ifdef DD_MM_FORCE
     return launch_mm<DD_MM_FORCE>(T, NC, KD, A, Wf, C, stream);  // tuning builds only
 #endif
+    const int64_t tiles160 = ((a.T + 159) / 160) * ((NC + 255) / 256);
     if (NC % 256 == 0) {
         // more tiles than CUs: one workgroup per CU walks its tiles with the pipeline kept running
-        const int64_t tiles160 = ((a.T + 159) / 160) * (NC / 256);
         if (tiles160 > 256) return launch_mm_persistent<160, 256, kMmWaves>(T, NC, KD, A, Wf, C, stream);
         switch (pick_tile(a.T, NC)) {
         case 192: return launch_mm<192, 256, kMmWaves>(T, NC, KD, A, Wf, C, stream);

@@ -19,6 +19,7 @@
 //             accumulator tile; repeated offsets read the same partial sums.
 #include "dd_common.h"
 #include "dd_launch.h"
+#include "dd_ring.h"
 
 #include <limits.h>
 
@@ -40,19 +41,6 @@ constexpr int kNoDiagonal = INT_MAX;
 constexpr int kWgXcds = 8;          // L2 caches (one per XCD); workgroups are dealt to them round-robin
 constexpr int kCusPerXcd = 32;
 constexpr int kWgPerCu = 2;         // two workgroups share a CU: one multiplies while the other waits for its slice
-
-// Sixteen bytes per lane from global memory straight into LDS: lane l of the wave lands at lds_base + 16 l.
-// lds_base is a byte address inside LDS and must be the same in every lane.  Written as assembly so that
-// the compiler does not serialise every later LDS read behind the transfer; completion is tracked by hand
-// with the vector-memory counter (transfers finish in issue order).
-__device__ __forceinline__ void global_to_lds_16(const void *g, unsigned lds_base)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(g) : "memory", "m0");
-}
-__device__ __forceinline__ unsigned lds_address(const void *p)
-{
-    return unsigned(reinterpret_cast<size_t>((__attribute__((address_space(3))) const char *)(p)));
-}
 
 // What the transfers of short-side rows past the end of a chunk read instead: a zero factor adds nothing.
 __device__ __align__(16) const unsigned int wg_zero_piece[4] = {0u, 0u, 0u, 0u};
@@ -76,27 +64,6 @@ struct WgTile {
     static constexpr int NF = FA + FB;             // fragments per k-step
     static_assert(TP % 64 == 0 && TQ % 64 == 0, "wave tiles are made of 32x32 MFMA tiles");
     static_assert(StageBytes % (16 * kWgT) == 0, "a stage is moved in whole rounds of the workgroup");
-};
-
-// Order of work inside a k-step.  Fragments are fetched A0, B0, A1, B1, ... and the MFMAs are taken in the
-// order in which their fragments arrive: by max(a, b).
-template <int FA, int FB>
-struct WgOrder {
-    int mfma_a[FA * FB], mfma_b[FA * FB];
-    int frag_is_a[FA + FB], frag_idx[FA + FB];
-    constexpr WgOrder() : mfma_a(), mfma_b(), frag_is_a(), frag_idx()
-    {
-        int n = 0;
-        for (int level = 0; level < (FA > FB ? FA : FB); ++level)
-            for (int a = 0; a < FA; ++a)
-                for (int b = 0; b < FB; ++b)
-                    if ((a > b ? a : b) == level) { mfma_a[n] = a; mfma_b[n] = b; ++n; }
-        int k = 0;
-        for (int i = 0; i < (FA > FB ? FA : FB); ++i) {
-            if (i < FA) { frag_is_a[k] = 1; frag_idx[k] = i; ++k; }
-            if (i < FB) { frag_is_a[k] = 0; frag_idx[k] = i; ++k; }
-        }
-    }
 };
 
 // Rows are not padded; instead the 16-byte pieces of row r are permuted by XOR with 2 * (r mod 4), so that
