@@ -52,7 +52,7 @@ size_t weight_grad_dot2_ws_bytes(int64_t T, int D, int L, int K);
 int weight_grad_dot2_chunks(int64_t T, int D, int L, int K);
 hipError_t launch_weight_grad_dot2_partials(const WeightGradArgs &a, hipStream_t stream);
 
-// matrix-core family (bf16 only, short side a multiple of 128, long side a multiple of 256)
+// matrix-core family (bf16 only, both feature counts multiples of 192 or both multiples of 128)
 bool weight_grad_matrix_supported(int64_t T, int D, int L, bool bf16);
 size_t weight_grad_matrix_ws_bytes(int64_t T, int D, int L, int K);
 hipError_t launch_weight_grad_matrix(const WeightGradArgs &a, hipStream_t stream);

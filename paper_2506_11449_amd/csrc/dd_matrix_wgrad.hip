@@ -275,9 +275,11 @@ __global__ __launch_bounds__(kWgT, kWgPerCu) void wgrad_mm_kernel(int T, int D, 
     // at once along the diagonal -- lane = (list slot, row mod 8) -- and leave as 32-byte runs of partial sums.
     constexpr int kTileStride = 36;  // floats per tile column: 16-byte aligned rows of four, odd diagonal stride
     constexpr int kTileFloats = 32 * kTileStride;
-    constexpr int kGroup = 3;
     constexpr int kTilesPerWave = Tl::FA * Tl::FB;
     constexpr int kWaveBytes = kWgRing * kStageBytes / 4;
+    constexpr int kRoom = (kWaveBytes - kTilesPerWave * 64 * 4) / (kTileFloats * 4);  // tile buffers beside the lists
+    constexpr int kGroup = kRoom < 3 ? kRoom : 3;
+    static_assert(kGroup >= 1, "at least one accumulator tile at a time");
     static_assert(kGroup * kTileFloats * 4 + kTilesPerWave * 64 * 4 <= kWaveBytes, "tile buffers and lists fit the wave's share of the stages");
     float *tilebuf = reinterpret_cast<float *>(smem + wave * kWaveBytes);                 // [kGroup][32 x 36]
     int *lists = reinterpret_cast<int *>(smem + wave * kWaveBytes) + kGroup * kTileFloats;  // [tiles][64]
@@ -422,8 +424,11 @@ struct WgradPlan {
 static WgradPlan plan_wgrad(int64_t T, int D, int L)
 {
     WgradPlan pl;
-    // 192 x 192 tiles keep the four waves square (96 x 96) and divide the ViT-Base widths; otherwise 128 x 256
-    if (L % 192 == 0 && D % 192 == 0) { pl.tp = 192; pl.tq = 192; } else { pl.tp = 128; pl.tq = 256; }
+    // 192 x 192 tiles keep the four waves square (96 x 96) and divide the ViT-Base widths; otherwise 128 x 256,
+    // and 128 x 128 where the long side is no multiple of 256
+    if (L % 192 == 0 && D % 192 == 0) { pl.tp = 192; pl.tq = 192; }
+    else if (D % 256 == 0) { pl.tp = 128; pl.tq = 256; }
+    else { pl.tp = 128; pl.tq = 128; }
     pl.tiles_p = L / pl.tp;
     pl.tiles_q = D / pl.tq;
     const int tiles = pl.tiles_p * pl.tiles_q;
@@ -443,7 +448,7 @@ static WgradPlan plan_wgrad(int64_t T, int D, int L)
 bool weight_grad_matrix_supported(int64_t T, int D, int L, bool bf16)
 {
     if (!(bf16 && T > 0 && T < (int64_t(1) << 31) && D <= 8192)) return false;
-    return (L % 192 == 0 && D % 192 == 0) || (L % 128 == 0 && D % 256 == 0);
+    return (L % 192 == 0 && D % 192 == 0) || (L % 128 == 0 && D % 128 == 0);
 }
 
 size_t weight_grad_matrix_ws_bytes(int64_t T, int D, int L, int K)
@@ -475,8 +480,9 @@ hipError_t launch_weight_grad_matrix(const WeightGradArgs &a, hipStream_t stream
 {
     const WgradPlan pl = plan_wgrad(a.T, a.D, a.L);
     float *partial = static_cast<float *>(a.ws);
-    hipError_t e = pl.tp == 192 ? launch_wgrad_mm<192, 192>(a, pl, partial, stream)
-                                : launch_wgrad_mm<128, 256>(a, pl, partial, stream);
+    hipError_t e = pl.tp == 192   ? launch_wgrad_mm<192, 192>(a, pl, partial, stream)
+                   : pl.tq == 256 ? launch_wgrad_mm<128, 256>(a, pl, partial, stream)
+                                  : launch_wgrad_mm<128, 128>(a, pl, partial, stream);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((a.L + 255) / 256, a.K), dim3(256), 0, stream, a.D, a.L, a.K,
                        pl.splits, a.offsets, partial, a.dValues);

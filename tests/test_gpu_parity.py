@@ -34,6 +34,9 @@ SMALL = [
     (8192, 128, 100, 70),
     (2048, 2048, 20, 100),
     (384, 1152, 60, 333),
+    (256, 384, 38, 200),
+    (640, 128, 30, 77),
+    (192, 576, 50, 130),
     (33, 7, 4, 19),
     (7, 33, 4, 19),
     (1, 1, 1, 5),
@@ -44,6 +47,12 @@ SMALL = [
 def matrix_shape_ok(M, N, dtype):
     """Shapes the matrix-core kernels cover: bf16 storage, both feature counts multiples of 128."""
     return dtype == "bf16" and M % 128 == 0 and N % 128 == 0 and max(M, N) <= 8192
+
+
+def matrix_wgrad_shape_ok(M, N, dtype):
+    """The matrix-core weight gradient tiles 192 x 192, 128 x 256 or 128 x 128."""
+    both = lambda d: M % d == 0 and N % d == 0
+    return dtype == "bf16" and (both(192) or both(128)) and max(M, N) <= 8192
 
 
 def _call(fn, *args, algo):
@@ -68,6 +77,7 @@ def run_all(offsets, values, X, dY, dtype, algo):
     if algo == dd.DD_ALGO_MATRIX:
         ok = matrix_shape_ok(M, N, dtype) and T > 0
         assert (Y is not None) == ok and (dX is not None) == ok
+        assert (dV is not None) == (matrix_wgrad_shape_ok(M, N, dtype) and T > 0)
     else:
         assert Y is not None and dX is not None and dV is not None
     return tuple(None if r is None else to_host(r) for r in (Y, dX, dV))
