@@ -35,6 +35,8 @@ SMALL = [
     (2048, 2048, 20, 100),
     (384, 1152, 60, 333),
     (256, 384, 38, 200),
+    (2048, 2048, 1500, 100),
+    (256, 256, 256, 90),
     (640, 128, 30, 77),
     (192, 576, 50, 130),
     (33, 7, 4, 19),
