@@ -13,7 +13,9 @@
 // Step 2 (mm_kernel): C [T x NC] = A [T x KD] . W with v_mfma_f32_32x32x16_bf16.  A workgroup of
 //   NW waves (eight by default: two per SIMD, so that one wave's waits hide behind the other's
 //   MFMAs) owns a BM x BN tile of C; each wave owns BN/NW output columns (its weight fragments
-//   are private, loaded global -> registers one k-slice ahead) and all BM tokens.  The token
+//   are private, loaded global -> registers one k-slice ahead) and all BM tokens.  All waves run in
+//   step from barrier to barrier, so every other instruction of a k-slice (fragment reads, weight
+//   loads, token pieces to LDS, new requests) is dealt out between the MFMAs instead of in phases.  The token
 //   operand is shared by all waves and goes through a three-deep LDS ring in 64-wide k-slices,
 //   XOR-swizzled in 16-byte chunks so that fragment reads are free of bank conflicts.
 //   The MFMA rows are output columns and the MFMA columns are tokens, which leaves every lane
@@ -211,24 +213,38 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
             acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf_[ks_][a], xf_[b], acc[a][b], 0, 0, 0);
     // One k-slice: four k-steps; the token fragments of the next k-step are fetched from LDS while
     // the current one is multiplied; then the slice two ahead is parked in LDS and a new one requested.
+    // one k-step: after each MFMA the token fragment of the following k-step for the same token tile, and one
+    // piece of the slice's other traffic (weight fragments of the next slice, token pieces into LDS, new requests)
+#define DD_XF_ONE(xf_, kt_, ks_, b_)                                                                    \
+    xf_[b_] = *reinterpret_cast<const bf16x8 *>(smem + ((kt_) % kRing) * Tl::X_BYTES + b_off[b_] +      \
+                                                 ((((ks_) * 2 + half) ^ b_sw[b_]) << 4));
+#define DD_STEP(wf_cur_, ks_, xf_cur_, xf_nxt_, kt_nxt_, ks_nxt_, extra_)                               \
+    _Pragma("unroll") for (int b = 0; b < Tl::FB; ++b) {                                                \
+        _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a)                                              \
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf_cur_[ks_][a], xf_cur_[b], acc[a][b], 0, 0, 0); \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        DD_XF_ONE(xf_nxt_, kt_nxt_, ks_nxt_, b)                                                         \
+        extra_                                                                                          \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+    }
 #define DD_SLICE(kt_, wf_cur_, wf_next_, xg_)                                                           \
-    DD_LOAD_W(wf_next_, (kt_) + 1)                                                                      \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_LOAD_XF(xf1, kt_, 1)                                                                             \
-    DD_MFMA(wf_cur_, 0, xf0)                                                                            \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_LOAD_XF(xf0, kt_, 2)                                                                             \
-    DD_MFMA(wf_cur_, 1, xf1)                                                                            \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_LOAD_XF(xf1, kt_, 3)                                                                             \
-    DD_MFMA(wf_cur_, 2, xf0)                                                                            \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_LOAD_XF(xf0, (kt_) + 1, 0)                                                                       \
-    DD_MFMA(wf_cur_, 3, xf1)                                                                            \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_STORE_X(xg_, (kt_) + 2)                                                                          \
-    DD_LOAD_X(xg_, (kt_) + 4)                                                                           \
-    __syncthreads();
+    {                                                                                                   \
+        const int gmax = KD / 64 - 1;                                                                   \
+        const size_t w_kk = size_t(((kt_) + 1) < gmax ? ((kt_) + 1) : gmax) * 4 * 512;                  \
+        const int x_kk = (((kt_) + 4) < KT ? ((kt_) + 4) : KT - 1) * kBK;                               \
+        unsigned char *x_dstb = smem + (((kt_) + 2) % kRing) * Tl::X_BYTES;                             \
+        DD_STEP(wf_cur_, 0, xf0, xf1, kt_, 1,                                                           \
+                if (b < 2) { _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a) {                       \
+                    wf_next_[2 * b][a] = *reinterpret_cast<const bf16x8 *>(w_src[a] + w_kk + (2 * b) * 512); \
+                    wf_next_[2 * b + 1][a] = *reinterpret_cast<const bf16x8 *>(w_src[a] + w_kk + (2 * b + 1) * 512); } }) \
+        DD_STEP(wf_cur_, 1, xf1, xf0, kt_, 2, )                                                         \
+        DD_STEP(wf_cur_, 2, xf0, xf1, kt_, 3,                                                           \
+                if (b < Tl::X_CHUNKS) { *reinterpret_cast<u32x4 *>(x_dstb + x_dst[b]) = xg_[b];         \
+                                        xg_[b] = *reinterpret_cast<const u32x4 *>(x_src[b] + x_kk); })  \
+        DD_STEP(wf_cur_, 3, xf1, xf0, (kt_) + 1, 0, )                                                   \
+        __syncthreads();                                                                                \
+    }
+    static_assert(Tl::X_CHUNKS <= Tl::FB && Tl::FB >= 2, "one extra piece of work per MFMA");
 
     // prologue: slices 0 and 1 in LDS, slices 2 and 3 in flight, weight fragments of slice 0 loaded
     DD_LOAD_X(xg0, 0)
@@ -250,6 +266,8 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
 #undef DD_LOAD_XF
 #undef DD_MFMA
 #undef DD_SLICE
+#undef DD_STEP
+#undef DD_XF_ONE
 
     // Epilogue.  Accumulator i of lane l is output column 8*(i/4) + 4*(l/32) + i%4 of token l%32
     // inside its 32x32 tile: four consecutive columns per group, written as one 8-byte LDS store.
@@ -384,24 +402,50 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
     _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a)                                                  \
         _Pragma("unroll") for (int b = 0; b < Tl::FB; ++b)                                              \
             acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf_[ks_][a], xf_[b], acc[a][b], 0, 0, 0);
+#define DD_XF_ONE(xf_, g_, ks_, b_)                                                                     \
+    xf_[b_] = *reinterpret_cast<const bf16x8 *>(smem + ((g_) % kRing) * Tl::X_BYTES + b_off[b_] +       \
+                                                 ((((ks_) * 2 + half) ^ b_sw[b_]) << 4));
+    // one k-step: after each MFMA the token fragment of the following k-step for the same token tile, and one
+    // piece of the slice's other traffic
+#define DD_STEP(wf_cur_, ks_, xf_cur_, xf_nxt_, g_nxt_, ks_nxt_, extra_)                                \
+    _Pragma("unroll") for (int b = 0; b < Tl::FB; ++b) {                                                \
+        _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a)                                              \
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf_cur_[ks_][a], xf_cur_[b], acc[a][b], 0, 0, 0); \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        DD_XF_ONE(xf_nxt_, g_nxt_, ks_nxt_, b)                                                          \
+        extra_                                                                                          \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+    }
 #define DD_SLICE(g_, wf_cur_, wf_next_, xg_)                                                            \
-    DD_LOAD_W(wf_next_, (g_) + 1)                                                                       \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_LOAD_XF(xf1, g_, 1)                                                                              \
-    DD_MFMA(wf_cur_, 0, xf0)                                                                            \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_LOAD_XF(xf0, g_, 2)                                                                              \
-    DD_MFMA(wf_cur_, 1, xf1)                                                                            \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_LOAD_XF(xf1, g_, 3)                                                                              \
-    DD_MFMA(wf_cur_, 2, xf0)                                                                            \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_LOAD_XF(xf0, (g_) + 1, 0)                                                                        \
-    DD_MFMA(wf_cur_, 3, xf1)                                                                            \
-    __builtin_amdgcn_sched_barrier(0);                                                                  \
-    DD_STORE_X(xg_, (g_) + 2)                                                                           \
-    DD_LOAD_X(xg_, (g_) + 4)                                                                            \
-    __syncthreads();
+    {                                                                                                   \
+        const uint16_t *w_next[Tl::FA];                                                                 \
+        {                                                                                               \
+            DD_WHERE((g_) + 1)                                                                          \
+            (void)tm_of;                                                                                \
+            _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a)                                          \
+                w_next[a] = Wf + (size_t((tn_of * BN + wave * Tl::WN) / 32 + a) * (KD / 16) * 64 + lane) * 8 + \
+                            size_t(kt_in) * 4 * 512;                                                    \
+        }                                                                                               \
+        const uint16_t *x_next[Tl::X_CHUNKS];                                                           \
+        {                                                                                               \
+            DD_WHERE((g_) + 4)                                                                          \
+            (void)tn_of;                                                                                \
+            _Pragma("unroll") for (int n = 0; n < Tl::X_CHUNKS; ++n)                                    \
+                x_next[n] = A + size_t(min(tm_of * BM + x_row[n], T - 1)) * KD + x_col[n] + kt_in * kBK; \
+        }                                                                                               \
+        unsigned char *x_dstb = smem + (((g_) + 2) % kRing) * Tl::X_BYTES;                              \
+        DD_STEP(wf_cur_, 0, xf0, xf1, g_, 1,                                                            \
+                if (b < 2) { _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a) {                       \
+                    wf_next_[2 * b][a] = *reinterpret_cast<const bf16x8 *>(w_next[a] + (2 * b) * 512);  \
+                    wf_next_[2 * b + 1][a] = *reinterpret_cast<const bf16x8 *>(w_next[a] + (2 * b + 1) * 512); } }) \
+        DD_STEP(wf_cur_, 1, xf1, xf0, g_, 2, )                                                          \
+        DD_STEP(wf_cur_, 2, xf0, xf1, g_, 3,                                                            \
+                if (b < Tl::X_CHUNKS) { *reinterpret_cast<u32x4 *>(x_dstb + x_dst[b]) = xg_[b];         \
+                                        xg_[b] = *reinterpret_cast<const u32x4 *>(x_next[b]); })        \
+        DD_STEP(wf_cur_, 3, xf1, xf0, (g_) + 1, 0, )                                                    \
+        __syncthreads();                                                                                \
+    }
+    static_assert(Tl::X_CHUNKS <= Tl::FB && Tl::FB >= 2, "one extra piece of work per MFMA");
 
     DD_LOAD_X(xg0, 0)
     DD_LOAD_X(xg1, 1)
@@ -448,6 +492,8 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
             tile_lin += kSlots;
         }
     }
+#undef DD_STEP
+#undef DD_XF_ONE
 #undef DD_WHERE
 #undef DD_LOAD_X
 #undef DD_STORE_X
