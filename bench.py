@@ -72,7 +72,7 @@ def cpu_baseline(layer, offsets, values, X, dY, scores):
         orc.bwd_weight(X, dY, offsets)
         reps += 1
         dt = time.perf_counter() - t0
-        if dt > 10.0 or reps >= 5:
+        if dt > 10.0 or reps >= 40:
             break
     flops = 3 * 2.0 * layer.tokens * layer.K * layer.L * reps
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
@@ -233,7 +233,13 @@ def main():
                      "dense_equivalent_tflops": 2.0 * T * M * N / dom_s / 1e12,
                      "kernel": dominant, "avg_launch_us": dom_s * 1e6, "flops_per_launch": flops_product,
                      "bytes_per_launch": dom_bytes, "flop_per_byte": intensity,
-                     "achieved_tflops": flops_product / dom_s / 1e12, "achieved_gbs": dom_bytes / dom_s / 1e9})
+                     "achieved_tflops": flops_product / dom_s / 1e12, "achieved_gbs": dom_bytes / dom_s / 1e9,
+                     # the same fraction for each of the three products (the dominant one is the slowest)
+                     "frac_per_entry_point": {
+                         k: (flops_product / (per[k] * 1e-3) / 1e12 / VALU_FP32_PEAK_TFLOPS if alu_bound else
+                             (bytes_wgrad if k == "dd_bwd_weight" else bytes_product) / (per[k] * 1e-3) / 1e9
+                             / HBM_PEAK_GBS)
+                         for k in ("dd_fwd", "dd_bwd_input", "dd_bwd_weight")}})
 
     breakdown = {"us": {k: v * 1e3 for k, v in per.items()},
                  "us_self_contained": {k: v * 1e3 for k, v in alone.items()},
