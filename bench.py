@@ -270,6 +270,35 @@ def main():
                                                                                    ws=ws), S, n, 5)}
     breakdown["diagheur_path_us"] = {k: v * 1e3 for k, v in heur.items()}
 
+    # three layers of this shape reading one input (query, key, value of an attention block), outside the step:
+    # one call per product against one call per layer
+    if use_prepare:
+        G = 3
+        g_off = torch.stack([torch.from_numpy(synth.draw_offsets(D, K, seed=2506 + g)) for g in range(G)]).cuda()
+        g_val = torch.stack([d_val] * G).contiguous()
+        g_prep = dd.dd_prepare_shared(g_off, g_val, M, N)
+        one_prep = [dd.dd_prepare(g_off[g], g_val[g], M, N) for g in range(G)]
+        g_Y = [torch.empty((G, T, N), dtype=tdtype, device="cuda") for _ in range(S)]
+        g_dX = [torch.empty((G, T, M), dtype=tdtype, device="cuda") for _ in range(S)]
+
+        def per_layer_fwd(s):
+            for g in range(G):
+                dd.dd_fwd(d_X[s], None, None, N, Y=g_Y[s][g], prepared=one_prep[g])
+
+        def per_layer_bwd_input(s):  # without the two additions that would still have to follow
+            for g in range(G):
+                dd.dd_bwd_input(g_Y[s][g], None, None, M, dX=g_dX[s][g], prepared=one_prep[g])
+
+        shared = {"dd_prepare_shared": time_loop(torch, lambda s: dd.dd_prepare_shared(g_off, g_val, M, N, prepared=g_prep),
+                                                 S, n, 5),
+                  "dd_fwd_shared": time_loop(torch, lambda s: dd.dd_fwd_shared(d_X[s], g_prep, Y=g_Y[s]), S, n, 5),
+                  "dd_bwd_input_shared": time_loop(torch, lambda s: dd.dd_bwd_input_shared(g_Y[s], g_prep, dX=d_dX[s]),
+                                                   S, n, 5),
+                  "3 x dd_fwd": time_loop(torch, per_layer_fwd, S, n, 5),
+                  "3 x dd_bwd_input (unsummed)": time_loop(torch, per_layer_bwd_input, S, n, 5)}
+        breakdown["shared_input_3_sets_us"] = {k: v * 1e3 for k, v in shared.items()}
+        del g_Y, g_dX
+
     if not args.no_dense:
         # dense bf16 GEMMs of the same shape (hipBLASLt / rocBLAS via torch.matmul), same rotation
         Wd = torch.randn((M, N), device="cuda", dtype=tdtype) * 0.02

@@ -122,6 +122,30 @@ dd_status dd_bwd_input(const dd_layer *layer, const void *dY, const int32_t *off
                        const void *values, void *dX, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * A group of n_sets diagonally sparse layers of one shape (M -> N, K diagonals each) that read the same input,
+ * such as the query, key and value projections of an attention block where those are sparse (Sec. 4.3: GPT-2
+ * with attention and MLP layers sparse).  Set s is the layer of Sec. 3.1 Eq. 3 with its own offsets and values:
+ *   dd_fwd_shared        Y_s = X . W_s for every set, X read once;               Y  [n_sets][tokens x N] out
+ *   dd_bwd_input_shared  dX = sum_s dY_s . W_s^T, summed in fp32 in one contraction and rounded once
+ *                        (the gradient of the shared input);                     dY [n_sets][tokens x N] in
+ * The n_sets output (gradient) matrices lie one after the other, each row-major and contiguous, so each is a
+ * valid argument of dd_bwd_weight for its set.
+ *   dd_prepare_shared    offsets [n_sets x K], values [n_sets x K x L] in; builds the dense operands of both
+ *                        products for all sets into `prepared`: n_sets * dd_workspace_bytes(DD_OP_PREPARE, layer, 0)
+ *                        bytes, 256-byte aligned, owned by the caller, valid until offsets or values change.
+ *                        With n_sets = 1 the block equals the one dd_prepare fills.
+ * layer->algo is not read by the two products (they always take the prepared operands); n_sets is 1..8.
+ * DD_ERR_UNSUPPORTED where dd_prepare returns it, DD_ERR_WORKSPACE for a block that is too small or misaligned.
+ * On other shapes or dtypes call dd_fwd / dd_bwd_input once per set.
+ */
+dd_status dd_prepare_shared(const dd_layer *layer, int32_t n_sets, const int32_t *offsets, const void *values,
+                            void *prepared, size_t prepared_bytes, void *hip_stream);
+dd_status dd_fwd_shared(const dd_layer *layer, int32_t n_sets, const void *X, const void *prepared,
+                        size_t prepared_bytes, void *Y, void *hip_stream);
+dd_status dd_bwd_input_shared(const dd_layer *layer, int32_t n_sets, const void *dY, const void *prepared,
+                              size_t prepared_bytes, void *dX, void *hip_stream);
+
+/*
  * Backward product with respect to the values on the K diagonals (Fig. 3 h, i): the dense
  * gradient X^T . dY restricted to the entries each diagonal owns, i.e. a sum over tokens,
  *   dValues[k][p] = sum_t X[t, row(k,p)] * dY[t, col(k,p)].

@@ -16,7 +16,8 @@ DD_ALGO_AUTO, DD_ALGO_VECTOR, DD_ALGO_MATRIX, DD_ALGO_PREPARED = 0, 1, 2, 3
 DD_OP_FWD, DD_OP_BWD_INPUT, DD_OP_BWD_WEIGHT, DD_OP_SELECT, DD_OP_SCALE_VALUES_BWD, DD_OP_PREPARE = 0, 1, 2, 3, 4, 5
 DD_OP_DIAGHEUR = 6
 
-EXPORTS = ("dd_workspace_bytes", "dd_fwd", "dd_prepare", "dd_bwd_input", "dd_bwd_weight", "dd_select_diagonals",
+EXPORTS = ("dd_workspace_bytes", "dd_fwd", "dd_prepare", "dd_prepare_shared", "dd_fwd_shared", "dd_bwd_input_shared",
+           "dd_bwd_input", "dd_bwd_weight", "dd_select_diagonals",
            "dd_soft_topk", "dd_soft_topk_bwd", "dd_scale_values", "dd_scale_values_bwd", "dd_diag_magnitude",
            "dd_diagheur_update", "dd_status_string")
 
@@ -49,6 +50,9 @@ def load_library():
     lib.dd_workspace_bytes.restype = sz
     lib.dd_fwd.argtypes = [lp, vp, vp, vp, vp, vp, sz, vp]
     lib.dd_prepare.argtypes = [lp, vp, vp, vp, sz, vp]
+    lib.dd_prepare_shared.argtypes = [lp, i32, vp, vp, vp, sz, vp]
+    lib.dd_fwd_shared.argtypes = [lp, i32, vp, vp, sz, vp, vp]
+    lib.dd_bwd_input_shared.argtypes = [lp, i32, vp, vp, sz, vp, vp]
     lib.dd_bwd_input.argtypes = [lp, vp, vp, vp, vp, vp, sz, vp]
     lib.dd_bwd_weight.argtypes = [lp, vp, vp, vp, vp, vp, sz, vp]
     lib.dd_select_diagonals.argtypes = [i32, i32, i32, vp, vp, vp, sz, vp]
@@ -159,6 +163,63 @@ def dd_prepare(offsets, values, in_features, out_features, prepared=None, stream
         raise ValueError("prepared block belongs to another layer")
     _check(load_library().dd_prepare(ref, _ptr(offsets), _ptr(values), _ptr(prepared.buf), prepared.buf.numel(), _stream(stream)))
     return prepared
+
+
+class PreparedShared:
+    """The block dd_prepare_shared fills for a group of n_sets layers of one shape that share their input."""
+
+    def __init__(self, buf, n_sets, in_features, out_features, K, dtype):
+        self.buf, self.n_sets = buf, n_sets
+        self.in_features, self.out_features, self.K, self.dtype = in_features, out_features, K, dtype
+
+
+def dd_prepare_shared(offsets, values, in_features, out_features, prepared=None, stream=None):
+    """offsets int32 [S x K], values [S x K x min(M,N)]: the dense operands of dd_fwd_shared / dd_bwd_input_shared."""
+    M, N = int(in_features), int(out_features)
+    S, K = offsets.shape
+    _, ref, need = _plan(DD_OP_PREPARE, 0, M, N, K, values.dtype, DD_ALGO_PREPARED)
+    _dev(offsets, torch.int32, (S, K), "offsets")
+    _dev(values, values.dtype, (S, K, min(M, N)), "values")
+    if prepared is None:
+        prepared = PreparedShared(torch.empty(max(need * S, 1), dtype=torch.uint8, device=values.device), S, M, N, K,
+                                  values.dtype)
+    if (prepared.n_sets, prepared.in_features, prepared.out_features, prepared.K, prepared.dtype) != \
+            (S, M, N, K, values.dtype):
+        raise ValueError("prepared block belongs to another group of layers")
+    _check(load_library().dd_prepare_shared(ref, S, _ptr(offsets), _ptr(values), _ptr(prepared.buf),
+                                            prepared.buf.numel(), _stream(stream)))
+    return prepared
+
+
+def dd_fwd_shared(X, prepared, Y=None, stream=None):
+    """Y[s] = X . W_s for every set of the group: X [T x M] -> Y [S x T x N]."""
+    T, M, N, S = X.shape[0], prepared.in_features, prepared.out_features, prepared.n_sets
+    if prepared.dtype != X.dtype:
+        raise ValueError("prepared block belongs to another group of layers")
+    ref = make_layer(T, M, N, prepared.K, X.dtype, DD_ALGO_PREPARED)
+    _dev(X, X.dtype, (T, M), "X")
+    if Y is None:
+        Y = torch.empty((S, T, N), dtype=X.dtype, device=X.device)
+    _dev(Y, X.dtype, (S, T, N), "Y")
+    _check(load_library().dd_fwd_shared(ctypes.byref(ref), S, _ptr(X), _ptr(prepared.buf), prepared.buf.numel(), _ptr(Y),
+                                        _stream(stream)))
+    return Y
+
+
+def dd_bwd_input_shared(dY, prepared, dX=None, stream=None):
+    """dX = sum over the sets of dY[s] . W_s^T: dY [S x T x N] -> dX [T x M]."""
+    M, N, S = prepared.in_features, prepared.out_features, prepared.n_sets
+    T = dY.shape[1]
+    if prepared.dtype != dY.dtype:
+        raise ValueError("prepared block belongs to another group of layers")
+    ref = make_layer(T, M, N, prepared.K, dY.dtype, DD_ALGO_PREPARED)
+    _dev(dY, dY.dtype, (S, T, N), "dY")
+    if dX is None:
+        dX = torch.empty((T, M), dtype=dY.dtype, device=dY.device)
+    _dev(dX, dY.dtype, (T, M), "dX")
+    _check(load_library().dd_bwd_input_shared(ctypes.byref(ref), S, _ptr(dY), _ptr(prepared.buf), prepared.buf.numel(),
+                                              _ptr(dX), _stream(stream)))
+    return dX
 
 
 def _product(fn, op, src, offsets, values, n_src, n_dst, M, N, dst, algo, ws, stream, prepared, names):

@@ -51,7 +51,8 @@ bool aligned16(const void *p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0;
 bool wants_matrix(const dd_layer *l, const Shape &s)
 {
     if (l->algo == DD_ALGO_VECTOR) return false;
-    if (!dd::product_matrix_supported(l->tokens, s.D, s.L, l->dtype == DD_BF16)) return false;
+    // (a call without tokens launches nothing, whatever the family)
+    if (!dd::product_matrix_supported(l->tokens > 0 ? l->tokens : 1, s.D, s.L, l->dtype == DD_BF16)) return false;
     return l->algo == DD_ALGO_MATRIX || l->algo == DD_ALGO_PREPARED || int64_t(l->K) * 48 >= s.D;
 }
 
@@ -65,15 +66,18 @@ bool wants_matrix_wgrad(const dd_layer *l, const Shape &s)
     return l->algo == DD_ALGO_MATRIX || l->algo == DD_ALGO_PREPARED || int64_t(l->K) * 48 >= s.D;
 }
 
+constexpr int kMaxSets = 8;
+
+// `sets` > 1: a group of equally shaped layers sharing their input, operands prepared by dd_prepare_shared
 dd_status product(const dd_layer *l, const Shape &s, bool transposed, const void *src, const int32_t *offsets,
-                  const void *values, void *dst, void *ws, size_t ws_bytes, void *stream)
+                  const void *values, void *dst, void *ws, size_t ws_bytes, void *stream, int sets = 1)
 {
     const bool prepared = l->algo == DD_ALGO_PREPARED;
     if (!prepared && (!offsets || !values)) return DD_ERR_INVALID_ARG;
     if (l->tokens > 0 && (!src || !dst)) return DD_ERR_INVALID_ARG;
     bool matrix = wants_matrix(l, s);
     if (prepared && !matrix) return DD_ERR_UNSUPPORTED;
-    const size_t need = dd_workspace_bytes(transposed ? DD_OP_BWD_INPUT : DD_OP_FWD, l, 0);
+    const size_t need = dd_workspace_bytes(transposed ? DD_OP_BWD_INPUT : DD_OP_FWD, l, 0) * size_t(sets);
     if (dd_status st = check_ws(ws, ws_bytes, need)) return st;
     if (l->tokens == 0) return DD_OK;
     if (matrix && !(aligned16(src) && aligned16(dst))) matrix = false;  // 16-byte vector accesses
@@ -93,7 +97,8 @@ dd_status product(const dd_layer *l, const Shape &s, bool transposed, const void
     a.ws = ws;
     if (prepared) {
         a.prepared = true;
-        if (transposed) a.ws = static_cast<unsigned char *>(ws) + dd::product_matrix_ws_bytes(s.D, s.L);
+        if (transposed) a.ws = static_cast<unsigned char *>(ws) + dd::product_matrix_ws_bytes(s.D, s.L) * size_t(sets);
+        (transposed ? a.src_sets : a.dst_sets) = sets;
     }
     const hipError_t e = matrix ? dd::launch_product_matrix(a, static_cast<hipStream_t>(stream))
                                 : dd::launch_product_vector(a, static_cast<hipStream_t>(stream));
@@ -153,12 +158,52 @@ dd_status dd_prepare(const dd_layer *layer, const int32_t *offsets, const void *
     if (layer->algo == DD_ALGO_VECTOR) return DD_ERR_UNSUPPORTED;
     if (!dd::product_matrix_supported(1, s.D, s.L, layer->dtype == DD_BF16)) return DD_ERR_UNSUPPORTED;
     if (dd_status st = check_ws(prepared, prepared_bytes_given, prepared_bytes(s))) return st;
-    // the forward product is the masked gather when the layer expands (M <= N), else the plain gather
     unsigned char *first = static_cast<unsigned char *>(prepared);
-    unsigned char *second = first + dd::product_matrix_ws_bytes(s.D, s.L);
-    const hipError_t e = dd::launch_prepare_matrix(s.D, s.L, layer->K, offsets, values, s.expanding ? first : second,
-                                                   s.expanding ? second : first, static_cast<hipStream_t>(hip_stream));
+    const hipError_t e = dd::launch_prepare_matrix(s.D, s.L, layer->K, 1, s.expanding, offsets, values, first,
+                                                   first + dd::product_matrix_ws_bytes(s.D, s.L),
+                                                   static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? DD_OK : DD_ERR_HIP;
+}
+
+dd_status dd_prepare_shared(const dd_layer *layer, int32_t n_sets, const int32_t *offsets, const void *values,
+                            void *prepared, size_t prepared_bytes_given, void *hip_stream)
+{
+    Shape s;
+    if (dd_status st = check_layer(layer, &s)) return st;
+    if (n_sets < 1 || !offsets || !values) return DD_ERR_INVALID_ARG;
+    if (n_sets > kMaxSets || layer->algo == DD_ALGO_VECTOR) return DD_ERR_UNSUPPORTED;
+    if (!dd::product_matrix_supported(1, s.D, s.L, layer->dtype == DD_BF16)) return DD_ERR_UNSUPPORTED;
+    if (dd_status st = check_ws(prepared, prepared_bytes_given, prepared_bytes(s) * size_t(n_sets))) return st;
+    unsigned char *first = static_cast<unsigned char *>(prepared);
+    const hipError_t e = dd::launch_prepare_matrix(s.D, s.L, layer->K, n_sets, s.expanding, offsets, values, first,
+                                                   first + dd::product_matrix_ws_bytes(s.D, s.L) * size_t(n_sets),
+                                                   static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? DD_OK : DD_ERR_HIP;
+}
+
+static dd_status product_shared(const dd_layer *layer, int32_t n_sets, bool transposed, const void *src,
+                                const void *prepared, size_t prepared_bytes_given, void *dst, void *hip_stream)
+{
+    Shape s;
+    if (dd_status st = check_layer(layer, &s)) return st;
+    if (n_sets < 1) return DD_ERR_INVALID_ARG;
+    if (n_sets > kMaxSets) return DD_ERR_UNSUPPORTED;
+    dd_layer l = *layer;
+    l.algo = DD_ALGO_PREPARED;
+    return product(&l, s, transposed, src, nullptr, nullptr, dst, const_cast<void *>(prepared), prepared_bytes_given,
+                   hip_stream, n_sets);
+}
+
+dd_status dd_fwd_shared(const dd_layer *layer, int32_t n_sets, const void *X, const void *prepared,
+                        size_t prepared_bytes_given, void *Y, void *hip_stream)
+{
+    return product_shared(layer, n_sets, false, X, prepared, prepared_bytes_given, Y, hip_stream);
+}
+
+dd_status dd_bwd_input_shared(const dd_layer *layer, int32_t n_sets, const void *dY, const void *prepared,
+                              size_t prepared_bytes_given, void *dX, void *hip_stream)
+{
+    return product_shared(layer, n_sets, true, dY, prepared, prepared_bytes_given, dX, hip_stream);
 }
 
 dd_status dd_bwd_input(const dd_layer *layer, const void *dY, const int32_t *offsets, const void *values, void *dX,

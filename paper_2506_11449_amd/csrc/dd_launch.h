@@ -21,6 +21,10 @@ struct ProductArgs {
     void *dst;
     void *ws;             // scratch of the size the chosen kernel family asks for
     bool prepared = false;  // matrix family: ws already holds the dense operand of this product
+    // Matrix family, prepared operands only: a group of equally shaped layers that share their input.
+    // dst_sets > 1: dst is that many [T x cols] matrices one after the other, one per set (the forward product);
+    // src_sets > 1: src likewise, and the sets' products are summed into the one dst (the backward-input product).
+    int src_sets = 1, dst_sets = 1;
 };
 
 // dV[k][p] = sum_t A[t, p] * B[t, (p + o_k) mod D];  A [T x L] (short side), B [T x D] (long side)
@@ -41,9 +45,12 @@ hipError_t launch_product_vector(const ProductArgs &a, hipStream_t stream);
 bool product_matrix_supported(int64_t T, int D, int L, bool bf16);
 size_t product_matrix_ws_bytes(int D, int L);
 hipError_t launch_product_matrix(const ProductArgs &a, hipStream_t stream);
-// both dense operands in one launch: the masked-gather one at `masked_operand`, the gather one at `gather_operand`
-hipError_t launch_prepare_matrix(int D, int L, int K, const int32_t *offsets, const void *values,
-                                 void *masked_operand, void *gather_operand, hipStream_t stream);
+// Both dense operands of `sets` equally shaped layers (offsets [sets x K], values [sets x K x L]) in one launch:
+// the forward operands side by side at `forward_operand`, the backward-input operands stacked along the
+// contraction at `backward_operand`, sets * D * L elements each.
+hipError_t launch_prepare_matrix(int D, int L, int K, int sets, bool expanding, const int32_t *offsets,
+                                 const void *values, void *forward_operand, void *backward_operand,
+                                 hipStream_t stream);
 size_t weight_grad_vector_ws_bytes(int64_t T, int D, int L, int K, bool bf16);
 hipError_t launch_weight_grad_vector(const WeightGradArgs &a, hipStream_t stream);
 // bf16 dot-product kernel of the vector family (feature counts multiples of 8, long side <= 2304)

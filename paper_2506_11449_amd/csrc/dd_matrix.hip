@@ -56,6 +56,10 @@ __device__ __forceinline__ size_t fragment_index(int j, int i, int KD)
     return ((size_t(j >> 5) * (KD >> 4) + (i >> 4)) * 64 + (j & 31) + 32 * ((i >> 3) & 1)) * 8 + (i & 7);
 }
 
+struct OperandPlace {
+    int kd_total, col_step, k_step;
+};
+
 // ---------------------------------------------------------------------------------------------
 // Step 1: dense operand from the diagonals, one workgroup per output column r of the product.
 //   masked gather:  row r = q in [0, D), KD = L:  w[p] = sum_{k: (q - o_k) mod D = p < L} v_k[p]
@@ -63,17 +67,26 @@ __device__ __forceinline__ size_t fragment_index(int j, int i, int KD)
 // The first `masked_rows` workgroups build rows of the masked-gather operand, the others rows of the
 // gather operand (either count may be zero).  A row is summed in fp32 in LDS (repeated offsets add, Eq. 3)
 // and rounded to bf16 once.
+// blockIdx.y numbers the sets of a group of layers of one shape whose operands are stacked into one matrix
+// (set s uses offsets + s*K and values + s*K*L): an OperandPlace says where set s goes, s*col_step columns
+// to the right (the sets' outputs side by side) or s*k_step contraction indices down (their results summed),
+// inside a matrix of kd_total contraction indices.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void materialize_kernel(int D, int L, int K, int masked_rows,
                                                           const int *__restrict__ offsets,
                                                           const uint16_t *__restrict__ values,
                                                           uint16_t *__restrict__ Wf_masked,
-                                                          uint16_t *__restrict__ Wf_gather)
+                                                          uint16_t *__restrict__ Wf_gather, OperandPlace place_masked,
+                                                          OperandPlace place_gather)
 {
     extern __shared__ float row[];
     const bool long_major = int(blockIdx.x) < masked_rows;
     const int r = long_major ? blockIdx.x : blockIdx.x - masked_rows;
     const int KD = long_major ? L : D;
+    const int set = blockIdx.y;
+    offsets += size_t(set) * K;
+    values += size_t(set) * K * L;
+    const OperandPlace place = long_major ? place_masked : place_gather;
     uint16_t *Wf = long_major ? Wf_masked : Wf_gather;
     for (int c = threadIdx.x; c < KD; c += 256) row[c] = 0.f;
     __syncthreads();
@@ -95,12 +108,17 @@ __global__ __launch_bounds__(256) void materialize_kernel(int D, int L, int K, i
 #pragma unroll
         for (int e = 0; e < 4; ++e)
             v[e] = uint32_t(f32_to_bf16(row[c8 * 8 + 2 * e])) | (uint32_t(f32_to_bf16(row[c8 * 8 + 2 * e + 1])) << 16);
-        *reinterpret_cast<u32x4 *>(Wf + fragment_index(r, c8 * 8, KD)) = v;
+        *reinterpret_cast<u32x4 *>(Wf + fragment_index(r + set * place.col_step, c8 * 8 + set * place.k_step,
+                                                       place.kd_total)) = v;
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// Step 2: C [T x NC] = A [T x KD] . W,  W given fragment-major
+// Step 2: C [T x NC] = A [T x KD] . W,  W given fragment-major.
+// A and C may each be a stack of equally shaped row-major matrices (a group of layers that share
+// their input): A = KD / a_cols matrices [T x a_cols] one after the other, contraction index i in
+// matrix i / a_cols, column i % a_cols; C = NC / c_cols matrices [T x c_cols] likewise.  a_cols is
+// a multiple of the k-slice, c_cols of eight; a plain product has a_cols = KD and c_cols = NC.
 // ---------------------------------------------------------------------------------------------
 template <int BM, int BN, int NW>
 struct MmTile {
@@ -117,9 +135,34 @@ struct MmTile {
     static_assert((BM * 8) % 64 == 0, "a stage is filled by whole waves");
 };
 
+// Result tile (tm, tn), held row by row in LDS, to the stack of [T x c_cols] matrices C: 16-byte pieces, full-width
+// row segments.  A tile of BN <= 256 columns reaches into at most three matrices of 128 or more columns.
+template <int BM, int BN, int THREADS>
+__device__ __forceinline__ void store_tile(uint16_t *__restrict__ C, const unsigned char *tile, int tile_stride, int tm,
+                                           int tn, int T, int c_cols, int tid)
+{
+    constexpr int ROW_CHUNKS = BN / 8;
+    const int first_matrix = (tn * BN) / c_cols;
+    const int first_col = tn * BN - first_matrix * c_cols;
+    for (int idx = tid; idx < BM * ROW_CHUNKS; idx += THREADS) {
+        const int row = idx / ROW_CHUNKS, ch = idx % ROW_CHUNKS;
+        const int t = tm * BM + row;
+        int matrix = first_matrix, col = first_col + ch * 8;
+#pragma unroll
+        for (int hop = 0; hop < 2; ++hop)
+            if (col >= c_cols) {
+                col -= c_cols;
+                ++matrix;
+            }
+        if (t < T)
+            *reinterpret_cast<u32x4 *>(C + (size_t(matrix) * T + t) * c_cols + col) =
+                *reinterpret_cast<const u32x4 *>(tile + row * tile_stride + ch * 16);
+    }
+}
+
 template <int BM, int BN, int NW>
-__global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int tiles_m, int tiles_n,
-                                                        const uint16_t *__restrict__ A,
+__global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int a_cols, int c_cols, int tiles_m,
+                                                        int tiles_n, const uint16_t *__restrict__ A,
                                                         const uint16_t *__restrict__ Wf,
                                                         uint16_t *__restrict__ C)
 {
@@ -151,8 +194,23 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
         const int row = idx / kChunksPerRow, ch = idx % kChunksPerRow;
         int t = tm * BM + row;
         t = t < T ? t : T - 1;  // rows past the end re-read the last token; their results are not stored
-        x_src[n] = A + size_t(t) * KD + ch * 8;
+        x_src[n] = A + size_t(t) * a_cols + ch * 8;
         x_dst[n] = row * kRowBytes + swizzle(row, ch) * 16;
+    }
+    // Where the next k-slice to request starts, relative to a row's first element: 64 columns further on, or in
+    // the next matrix of the stack.  Past the last slice the cursor stays put (the loop then re-reads that slice).
+    size_t x_off = 0;
+    int x_in = 0, x_slice = 0;
+    const size_t x_jump = size_t(T - 1) * a_cols;
+#define DD_X_ADVANCE                                                                                    \
+    if (x_slice < KT - 1) {                                                                             \
+        ++x_slice;                                                                                      \
+        x_off += kBK;                                                                                   \
+        x_in += kBK;                                                                                    \
+        if (x_in == a_cols) {                                                                           \
+            x_in = 0;                                                                                   \
+            x_off += x_jump;                                                                            \
+        }                                                                                               \
     }
     // weight fragments of this wave: block row (tn*BN + wave*WN)/32 + a, 1 KB per k-step, 16 bytes per lane
     const uint16_t *w_src[Tl::FA];
@@ -180,11 +238,11 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
     bf16x8 wf0[4][Tl::FA], wf1[4][Tl::FA];             // weight fragments of the current / next k-slice
     bf16x8 xf0[Tl::FB], xf1[Tl::FB];                   // token fragments of the current / next k-step
 
-#define DD_LOAD_X(xg_, kt_)                                                                             \
+#define DD_LOAD_X(xg_) /* the slice under the cursor; the cursor moves on */                           \
     {                                                                                                   \
-        const int kk = ((kt_) < KT ? (kt_) : KT - 1) * kBK;                                             \
         _Pragma("unroll") for (int n = 0; n < Tl::X_CHUNKS; ++n)                                        \
-            xg_[n] = *reinterpret_cast<const u32x4 *>(x_src[n] + kk);                                   \
+            xg_[n] = *reinterpret_cast<const u32x4 *>(x_src[n] + x_off);                                \
+        DD_X_ADVANCE                                                                                    \
     }
 #define DD_STORE_X(xg_, kt_)                                                                            \
     {                                                                                                   \
@@ -231,7 +289,8 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
     {                                                                                                   \
         const int gmax = KD / 64 - 1;                                                                   \
         const size_t w_kk = size_t(((kt_) + 1) < gmax ? ((kt_) + 1) : gmax) * 4 * 512;                  \
-        const int x_kk = (((kt_) + 4) < KT ? ((kt_) + 4) : KT - 1) * kBK;                               \
+        const size_t x_kk = x_off; /* slice kt_ + 4 */                                                 \
+        DD_X_ADVANCE                                                                                    \
         unsigned char *x_dstb = smem + (((kt_) + 2) % kRing) * Tl::X_BYTES;                             \
         DD_STEP(wf_cur_, 0, xf0, xf1, kt_, 1,                                                           \
                 if (b < 2) { _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a) {                       \
@@ -247,13 +306,13 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
     static_assert(Tl::X_CHUNKS <= Tl::FB && Tl::FB >= 2, "one extra piece of work per MFMA");
 
     // prologue: slices 0 and 1 in LDS, slices 2 and 3 in flight, weight fragments of slice 0 loaded
-    DD_LOAD_X(xg0, 0)
-    DD_LOAD_X(xg1, 1)
+    DD_LOAD_X(xg0)
+    DD_LOAD_X(xg1)
     DD_LOAD_W(wf0, 0)
     DD_STORE_X(xg0, 0)
     DD_STORE_X(xg1, 1)
-    DD_LOAD_X(xg0, 2)
-    DD_LOAD_X(xg1, 3)
+    DD_LOAD_X(xg0)
+    DD_LOAD_X(xg1)
     __syncthreads();
     DD_LOAD_XF(xf0, 0, 0)
     for (int kt = 0; kt < KT; kt += 2) {
@@ -261,6 +320,7 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
         DD_SLICE(kt + 1, wf1, wf0, xg1)
     }
 #undef DD_LOAD_X
+#undef DD_X_ADVANCE
 #undef DD_STORE_X
 #undef DD_LOAD_W
 #undef DD_LOAD_XF
@@ -285,14 +345,7 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
                 *reinterpret_cast<bf16x4 *>(smem + t_local * Tl::C_STRIDE + j_local * 2) = h;
             }
     __syncthreads();
-    constexpr int ROW_CHUNKS = BN / 8;
-    for (int idx = tid; idx < BM * ROW_CHUNKS; idx += kMmThreads) {
-        const int row = idx / ROW_CHUNKS, ch = idx % ROW_CHUNKS;
-        const int t = tm * BM + row;
-        if (t < T)
-            *reinterpret_cast<u32x4 *>(C + size_t(t) * NC + tn * BN + ch * 8) =
-                *reinterpret_cast<const u32x4 *>(smem + row * Tl::C_STRIDE + ch * 16);
-    }
+    store_tile<BM, BN, kMmThreads>(C, smem, Tl::C_STRIDE, tm, tn, T, c_cols, tid);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -303,7 +356,8 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
 // another fill of the pipeline.  The result tile has an LDS buffer of its own beside the ring.
 // ---------------------------------------------------------------------------------------------
 template <int BM, int BN, int NW>
-__global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, int KD, int tiles_m, int tiles_n,
+__global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, int KD, int a_cols, int c_cols,
+                                                                  int tiles_m, int tiles_n,
                                                                   const uint16_t *__restrict__ A,
                                                                   const uint16_t *__restrict__ Wf,
                                                                   uint16_t *__restrict__ C)
@@ -359,20 +413,54 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
     bf16x8 wf0[4][Tl::FA], wf1[4][Tl::FA];
     bf16x8 xf0[Tl::FB], xf1[Tl::FB];
 
-    // slice g_ (clamped to the last one) -> its tile and its place in it
-#define DD_WHERE(g_)                                                                                    \
-    const int g_c = (g_) < total ? (g_) : total - 1;                                                    \
-    const int lin = first + (g_c / KT) * kSlots;                                                        \
-    const int kt_in = g_c % KT;                                                                         \
-    const int tm_of = lin / tiles_n, tn_of = lin % tiles_n;
-#define DD_LOAD_X(xg_, g_)                                                                              \
+    // Two cursors walk the k-slices of this workgroup's tiles in order, one for the weight fragments (one slice
+    // ahead of the multiplication) and one for the token slices (four ahead).  They hold uniform values only and
+    // move without divisions or branches.  After the last slice of the last tile a cursor walks that tile again:
+    // the requests past the end only have to name valid addresses, what they fetch is never multiplied.
+    struct Cursor {
+        int tiles_left;  // my tiles after this one
+        int kt;          // k-slice inside the tile
+        int tm, tn;      // the tile
+        int set;         // matrix of the stack A that holds this slice
+        int set_col;     // first contraction index of the slice inside that matrix
+    };
+    const int hop_m = kSlots / tiles_n, hop_n = kSlots % tiles_n;  // from one of my tiles to the next
+    Cursor wc = {n_mine - 1, 0, first / tiles_n, first % tiles_n, 0, 0};
+    Cursor xc = wc;
+    int out_tm = wc.tm, out_tn = wc.tn;  // the tile being multiplied
+#define DD_ADVANCE(c_) /* selects only: a branch here would split the loop body */                      \
     {                                                                                                   \
-        DD_WHERE(g_)                                                                                    \
-        (void)tn_of;                                                                                    \
-        _Pragma("unroll") for (int n = 0; n < Tl::X_CHUNKS; ++n) {                                      \
-            const int t = min(tm_of * BM + x_row[n], T - 1); /* rows past the end re-read the last token */ \
-            xg_[n] = *reinterpret_cast<const u32x4 *>(A + size_t(t) * KD + x_col[n] + kt_in * kBK);     \
-        }                                                                                               \
+        const int wrap = c_.kt + 1 == KT ? 1 : 0;                                                       \
+        const int move = wrap & (c_.tiles_left > 0 ? 1 : 0);                                            \
+        const int carry = c_.tn + hop_n >= tiles_n ? 1 : 0;                                             \
+        const int next_set = c_.set_col + kBK == a_cols ? 1 : 0;                                        \
+        const int tn1 = c_.tn + hop_n - carry * tiles_n, tm1 = c_.tm + hop_m + carry;                   \
+        c_.tn = move ? tn1 : c_.tn;                                                                     \
+        c_.tm = move ? tm1 : c_.tm;                                                                     \
+        c_.tiles_left -= move;                                                                          \
+        c_.set = (c_.set + next_set) * (1 - wrap);                                                      \
+        c_.set_col = (c_.set_col + kBK) * (1 - (wrap | next_set));                                      \
+        c_.kt = (c_.kt + 1) * (1 - wrap);                                                               \
+    }
+    // The token slice under xc, piece n of this thread (rows past the end re-read the last token), and the weight
+    // fragments under wc, k-step 0 of the slice, fragment row a_ of this wave: a uniform part that the scalar unit
+    // works out, plus one 32 x 32 -> 64 bit multiply-add (tokens) or a per-lane constant (weights).
+    size_t w_lane[Tl::FA];
+#pragma unroll
+    for (int a = 0; a < Tl::FA; ++a) w_lane[a] = (size_t(wave * (Tl::WN / 32) + a) * (KD / 16) * 64 + lane) * 8;
+    const size_t w_tile_step = size_t(BN / 32) * (KD / 16) * 512;  // from one column tile to the next
+    const size_t a_matrix = size_t(T) * a_cols;                    // from one matrix of the stack to the next
+#define DD_X_AT(n_)                                                                                     \
+    (A + (size_t(xc.set) * a_matrix + xc.set_col + x_col[n_]) +                                         \
+     size_t(unsigned(min(xc.tm * BM + x_row[n_], T - 1))) * unsigned(a_cols))
+#define DD_W_AT(a_) (Wf + (size_t(wc.tn) * w_tile_step + size_t(wc.kt) * 4 * 512) + w_lane[a_])
+    const uint16_t *x_ptr[Tl::X_CHUNKS];  // where the next token slice to request starts, piece by piece
+    const uint16_t *w_ptr[Tl::FA];        // where the next weight fragments to request start
+#define DD_LOAD_X(xg_) /* the slice under the cursor; the cursor moves on */                           \
+    {                                                                                                   \
+        _Pragma("unroll") for (int n = 0; n < Tl::X_CHUNKS; ++n)                                        \
+            xg_[n] = *reinterpret_cast<const u32x4 *>(DD_X_AT(n));                                      \
+        DD_ADVANCE(xc)                                                                                  \
     }
 #define DD_STORE_X(xg_, g_)                                                                             \
     {                                                                                                   \
@@ -380,16 +468,14 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
         _Pragma("unroll") for (int n = 0; n < Tl::X_CHUNKS; ++n)                                        \
             *reinterpret_cast<u32x4 *>(dstb + x_dst[n]) = xg_[n];                                       \
     }
-#define DD_LOAD_W(wf_, g_)                                                                              \
+#define DD_LOAD_W(wf_)                                                                                  \
     {                                                                                                   \
-        DD_WHERE(g_)                                                                                    \
-        (void)tm_of;                                                                                    \
         _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a) {                                            \
-            const uint16_t *w = Wf + (size_t((tn_of * BN + wave * Tl::WN) / 32 + a) * (KD / 16) * 64 + lane) * 8 + \
-                                size_t(kt_in) * 4 * 512;                                                \
+            const uint16_t *w = DD_W_AT(a);                                                             \
             _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                            \
                 wf_[ks][a] = *reinterpret_cast<const bf16x8 *>(w + ks * 512);                           \
         }                                                                                               \
+        DD_ADVANCE(wc)                                                                                  \
     }
 #define DD_LOAD_XF(xf_, g_, ks_)                                                                        \
     {                                                                                                   \
@@ -416,53 +502,49 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
         extra_                                                                                          \
         __builtin_amdgcn_sched_barrier(0);                                                              \
     }
+    // One k-slice.  Its requests (weight fragments of slice g_ + 1, token slice g_ + 4) go to addresses worked out
+    // during the slice before, and the addresses for the slice after are worked out between its MFMAs, once the
+    // requests that use the old ones are out: no address arithmetic stands between the barrier and the first MFMA.
 #define DD_SLICE(g_, wf_cur_, wf_next_, xg_)                                                            \
     {                                                                                                   \
-        const uint16_t *w_next[Tl::FA];                                                                 \
-        {                                                                                               \
-            DD_WHERE((g_) + 1)                                                                          \
-            (void)tm_of;                                                                                \
-            _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a)                                          \
-                w_next[a] = Wf + (size_t((tn_of * BN + wave * Tl::WN) / 32 + a) * (KD / 16) * 64 + lane) * 8 + \
-                            size_t(kt_in) * 4 * 512;                                                    \
-        }                                                                                               \
-        const uint16_t *x_next[Tl::X_CHUNKS];                                                           \
-        {                                                                                               \
-            DD_WHERE((g_) + 4)                                                                          \
-            (void)tn_of;                                                                                \
-            _Pragma("unroll") for (int n = 0; n < Tl::X_CHUNKS; ++n)                                    \
-                x_next[n] = A + size_t(min(tm_of * BM + x_row[n], T - 1)) * KD + x_col[n] + kt_in * kBK; \
-        }                                                                                               \
         unsigned char *x_dstb = smem + (((g_) + 2) % kRing) * Tl::X_BYTES;                              \
         DD_STEP(wf_cur_, 0, xf0, xf1, g_, 1,                                                            \
                 if (b < 2) { _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a) {                       \
-                    wf_next_[2 * b][a] = *reinterpret_cast<const bf16x8 *>(w_next[a] + (2 * b) * 512);  \
-                    wf_next_[2 * b + 1][a] = *reinterpret_cast<const bf16x8 *>(w_next[a] + (2 * b + 1) * 512); } }) \
-        DD_STEP(wf_cur_, 1, xf1, xf0, g_, 2, )                                                          \
+                    wf_next_[2 * b][a] = *reinterpret_cast<const bf16x8 *>(w_ptr[a] + (2 * b) * 512);   \
+                    wf_next_[2 * b + 1][a] = *reinterpret_cast<const bf16x8 *>(w_ptr[a] + (2 * b + 1) * 512); } }) \
+        DD_STEP(wf_cur_, 1, xf1, xf0, g_, 2,                                                            \
+                if (b == 0) DD_ADVANCE(wc)                                                              \
+                if (b == 1) { _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a) w_ptr[a] = DD_W_AT(a); }) \
         DD_STEP(wf_cur_, 2, xf0, xf1, g_, 3,                                                            \
                 if (b < Tl::X_CHUNKS) { *reinterpret_cast<u32x4 *>(x_dstb + x_dst[b]) = xg_[b];         \
-                                        xg_[b] = *reinterpret_cast<const u32x4 *>(x_next[b]); })        \
-        DD_STEP(wf_cur_, 3, xf1, xf0, (g_) + 1, 0, )                                                    \
+                                        xg_[b] = *reinterpret_cast<const u32x4 *>(x_ptr[b]); })         \
+        DD_STEP(wf_cur_, 3, xf1, xf0, (g_) + 1, 0,                                                      \
+                if (b == 0) DD_ADVANCE(xc)                                                              \
+                if (b >= 1 && b - 1 < Tl::X_CHUNKS) x_ptr[b - 1] = DD_X_AT(b - 1);)                     \
         __syncthreads();                                                                                \
     }
-    static_assert(Tl::X_CHUNKS <= Tl::FB && Tl::FB >= 2, "one extra piece of work per MFMA");
+    static_assert(Tl::X_CHUNKS + 1 <= Tl::FB && Tl::FB >= 2, "one extra piece of work per MFMA");
 
-    DD_LOAD_X(xg0, 0)
-    DD_LOAD_X(xg1, 1)
-    DD_LOAD_W(wf0, 0)
+    DD_LOAD_X(xg0)
+    DD_LOAD_X(xg1)
+    DD_LOAD_W(wf0)
     DD_STORE_X(xg0, 0)
     DD_STORE_X(xg1, 1)
-    DD_LOAD_X(xg0, 2)
-    DD_LOAD_X(xg1, 3)
+    DD_LOAD_X(xg0)
+    DD_LOAD_X(xg1)
+#pragma unroll
+    for (int a = 0; a < Tl::FA; ++a) w_ptr[a] = DD_W_AT(a);  // slice 1
+#pragma unroll
+    for (int n = 0; n < Tl::X_CHUNKS; ++n) x_ptr[n] = DD_X_AT(n);  // slice 4
     __syncthreads();
     DD_LOAD_XF(xf0, 0, 0)
-    int kt = 0, tile_lin = first;
+    int kt = 0;
     for (int g = 0; g < total; g += 2) {
         DD_SLICE(g, wf0, wf1, xg0)
         DD_SLICE(g + 1, wf1, wf0, xg1)
         kt += 2;
         if (kt == KT) {  // uniform: the tile is complete
-            const int tm = tile_lin / tiles_n, tn = tile_lin % tiles_n;
+            const int tm = out_tm, tn = out_tn;
             // Accumulator i of lane l is output column 8*(i/4) + 4*(l/32) + i%4 of token l%32 inside its 32x32
             // tile.  (The copy-out of the previous tile finished before the barriers of this tile's slices.)
 #pragma unroll
@@ -480,21 +562,18 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
                         for (int i = 0; i < 4; ++i) acc[a][b][4 * q + i] = 0.f;
                     }
             __syncthreads();
-            constexpr int ROW_CHUNKS = BN / 8;
-            for (int idx = tid; idx < BM * ROW_CHUNKS; idx += kMmThreads) {
-                const int row = idx / ROW_CHUNKS, ch = idx % ROW_CHUNKS;
-                const int t = tm * BM + row;
-                if (t < T)
-                    *reinterpret_cast<u32x4 *>(C + size_t(t) * NC + tn * BN + ch * 8) =
-                        *reinterpret_cast<const u32x4 *>(c_buf + row * Tl::C_STRIDE + ch * 16);
-            }
+            store_tile<BM, BN, kMmThreads>(C, c_buf, Tl::C_STRIDE, tm, tn, T, c_cols, tid);
             kt = 0;
-            tile_lin += kSlots;
+            const bool carry = out_tn + hop_n >= tiles_n;
+            out_tn += hop_n - (carry ? tiles_n : 0);
+            out_tm += hop_m + (carry ? 1 : 0);
         }
     }
 #undef DD_STEP
 #undef DD_XF_ONE
-#undef DD_WHERE
+#undef DD_ADVANCE
+#undef DD_X_AT
+#undef DD_W_AT
 #undef DD_LOAD_X
 #undef DD_STORE_X
 #undef DD_LOAD_W
@@ -514,8 +593,8 @@ bool product_matrix_supported(int64_t T, int D, int L, bool bf16)
 size_t product_matrix_ws_bytes(int D, int L) { return size_t(D) * size_t(L) * 2; }
 
 template <int BM, int BN, int NW>
-static hipError_t launch_mm(int T, int NC, int KD, const uint16_t *A, const uint16_t *Wf, uint16_t *C,
-                            hipStream_t stream)
+static hipError_t launch_mm(int T, int NC, int KD, int a_cols, int c_cols, const uint16_t *A, const uint16_t *Wf,
+                            uint16_t *C, hipStream_t stream)
 {
     using Tl = MmTile<BM, BN, NW>;
     static bool configured = false;
@@ -528,22 +607,29 @@ static hipError_t launch_mm(int T, int NC, int KD, const uint16_t *A, const uint
     const int tiles_m = (T + BM - 1) / BM, tiles_n = NC / BN;
     const int per_xcd = (tiles_m * tiles_n + kXcds - 1) / kXcds;
     hipLaunchKernelGGL((mm_kernel<BM, BN, NW>), dim3(per_xcd * kXcds), dim3(Tl::THREADS), Tl::LDS_BYTES, stream, T, NC, KD,
-                       tiles_m, tiles_n, A, Wf, C);
+                       a_cols, c_cols, tiles_m, tiles_n, A, Wf, C);
     return hipGetLastError();
 }
 
-hipError_t launch_prepare_matrix(int D, int L, int K, const int32_t *offsets, const void *values, void *masked_operand,
-                                 void *gather_operand, hipStream_t stream)
+hipError_t launch_prepare_matrix(int D, int L, int K, int sets, bool expanding, const int32_t *offsets,
+                                 const void *values, void *forward_operand, void *backward_operand, hipStream_t stream)
 {
-    hipLaunchKernelGGL(materialize_kernel, dim3(D + L), dim3(256), size_t(D) * sizeof(float), stream, D, L, K, D, offsets,
-                       static_cast<const uint16_t *>(values), static_cast<uint16_t *>(masked_operand),
-                       static_cast<uint16_t *>(gather_operand));
+    // The forward product is the masked gather when the layer expands (M <= N), else the plain gather.  The sets'
+    // forward operands stand side by side (every set has outputs of its own), their backward-input operands on top
+    // of each other (the sets' contributions to the one input gradient add up in the contraction).
+    const OperandPlace side_by_side = {expanding ? L : D, expanding ? D : L, 0};
+    const OperandPlace stacked = {sets * (expanding ? D : L), 0, expanding ? D : L};
+    hipLaunchKernelGGL(materialize_kernel, dim3(D + L, sets), dim3(256), size_t(D) * sizeof(float), stream, D, L, K, D,
+                       offsets, static_cast<const uint16_t *>(values),
+                       static_cast<uint16_t *>(expanding ? forward_operand : backward_operand),
+                       static_cast<uint16_t *>(expanding ? backward_operand : forward_operand),
+                       expanding ? side_by_side : stacked, expanding ? stacked : side_by_side);
     return hipGetLastError();
 }
 
 template <int BM, int BN, int NW>
-static hipError_t launch_mm_persistent(int T, int NC, int KD, const uint16_t *A, const uint16_t *Wf, uint16_t *C,
-                                       hipStream_t stream)
+static hipError_t launch_mm_persistent(int T, int NC, int KD, int a_cols, int c_cols, const uint16_t *A,
+                                       const uint16_t *Wf, uint16_t *C, hipStream_t stream)
 {
     using Tl = MmTile<BM, BN, NW>;
     constexpr int kLds = kRing * Tl::X_BYTES + Tl::C_BYTES;
@@ -557,7 +643,7 @@ static hipError_t launch_mm_persistent(int T, int NC, int KD, const uint16_t *A,
     }
     const int tiles_m = (T + BM - 1) / BM, tiles_n = NC / BN;
     hipLaunchKernelGGL((mm_persistent_kernel<BM, BN, NW>), dim3(256), dim3(Tl::THREADS), kLds, stream, T, NC, KD,
-                       tiles_m, tiles_n, A, Wf, C);
+                       a_cols, c_cols, tiles_m, tiles_n, A, Wf, C);
     return hipGetLastError();
 }
 
@@ -583,12 +669,17 @@ static int pick_tile(int64_t T, int NC)
 hipError_t launch_product_matrix(const ProductArgs &a, hipStream_t stream)
 {
     // masked gather: dst has D columns, contraction over the L columns of src  -> operand rows are long-side
-    const int NC = a.masked ? a.D : a.L;
-    const int KD = a.masked ? a.L : a.D;
+    const int c_cols = a.masked ? a.D : a.L;
+    const int a_cols = a.masked ? a.L : a.D;
+    // a group of layers sharing their input: the sets' results side by side, or their contributions summed
+    const int NC = c_cols * a.dst_sets;
+    const int KD = a_cols * a.src_sets;
     uint16_t *Wf = static_cast<uint16_t *>(a.ws);
     if (!a.prepared) {
+        if (a.src_sets != 1 || a.dst_sets != 1) return hipErrorInvalidValue;  // groups come prepared
+        const OperandPlace place = {KD, 0, 0};
         hipLaunchKernelGGL(materialize_kernel, dim3(NC), dim3(256), size_t(KD) * sizeof(float), stream, a.D, a.L, a.K,
-                           a.masked ? NC : 0, a.offsets, static_cast<const uint16_t *>(a.values), Wf, Wf);
+                           a.masked ? NC : 0, a.offsets, static_cast<const uint16_t *>(a.values), Wf, Wf, place, place);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -596,21 +687,21 @@ hipError_t launch_product_matrix(const ProductArgs &a, hipStream_t stream)
     uint16_t *C = static_cast<uint16_t *>(a.dst);
     const int T = int(a.T);
 #ifdef DD_MM_FORCE
-    return launch_mm<DD_MM_FORCE>(T, NC, KD, A, Wf, C, stream);  // tuning builds only
+    return launch_mm<DD_MM_FORCE>(T, NC, KD, a_cols, c_cols, A, Wf, C, stream);  // tuning builds only
 #endif
     const int64_t tiles160 = ((a.T + 159) / 160) * ((NC + 255) / 256);
     if (NC % 256 == 0) {
         // more tiles than CUs: one workgroup per CU walks its tiles with the pipeline kept running
-        if (tiles160 > 256) return launch_mm_persistent<160, 256, kMmWaves>(T, NC, KD, A, Wf, C, stream);
+        if (tiles160 > 256) return launch_mm_persistent<160, 256, kMmWaves>(T, NC, KD, a_cols, c_cols, A, Wf, C, stream);
         switch (pick_tile(a.T, NC)) {
-        case 192: return launch_mm<192, 256, kMmWaves>(T, NC, KD, A, Wf, C, stream);
-        case 160: return launch_mm<160, 256, kMmWaves>(T, NC, KD, A, Wf, C, stream);
-        case 128: return launch_mm<128, 256, kMmWaves>(T, NC, KD, A, Wf, C, stream);
-        case 96: return launch_mm<96, 256, kMmWaves>(T, NC, KD, A, Wf, C, stream);
-        default: return launch_mm<64, 256, kMmWaves>(T, NC, KD, A, Wf, C, stream);
+        case 192: return launch_mm<192, 256, kMmWaves>(T, NC, KD, a_cols, c_cols, A, Wf, C, stream);
+        case 160: return launch_mm<160, 256, kMmWaves>(T, NC, KD, a_cols, c_cols, A, Wf, C, stream);
+        case 128: return launch_mm<128, 256, kMmWaves>(T, NC, KD, a_cols, c_cols, A, Wf, C, stream);
+        case 96: return launch_mm<96, 256, kMmWaves>(T, NC, KD, a_cols, c_cols, A, Wf, C, stream);
+        default: return launch_mm<64, 256, kMmWaves>(T, NC, KD, a_cols, c_cols, A, Wf, C, stream);
         }
     }
-    return launch_mm<128, 128, 4>(T, NC, KD, A, Wf, C, stream);
+    return launch_mm<128, 128, 4>(T, NC, KD, a_cols, c_cols, A, Wf, C, stream);
 }
 
 }  // namespace dd

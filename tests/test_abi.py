@@ -111,6 +111,34 @@ def test_prepare_rules(lib):
     assert lib.dd_bwd_input(ctypes.byref(ok), one, None, None, one, ctypes.c_void_p(512), need - 1, None) == 3
 
 
+def test_shared_input_rules(lib):
+    one = ctypes.c_void_p(256)
+    blk = ctypes.c_void_p(512)
+    ok = _layer(T=100, M=768, N=768, K=30, dtype=1)
+    per_set = lib.dd_workspace_bytes(binding.DD_OP_PREPARE, ctypes.byref(ok), 0)
+    assert per_set == 2 * 768 * 768 * 2
+    assert lib.dd_prepare_shared(ctypes.byref(ok), 0, one, one, blk, 8 * per_set, None) == 1
+    assert lib.dd_prepare_shared(ctypes.byref(ok), 9, one, one, blk, 9 * per_set, None) == 2
+    assert lib.dd_prepare_shared(ctypes.byref(ok), 3, None, one, blk, 3 * per_set, None) == 1
+    assert lib.dd_prepare_shared(ctypes.byref(ok), 3, one, None, blk, 3 * per_set, None) == 1
+    assert lib.dd_prepare_shared(ctypes.byref(ok), 3, one, one, blk, 3 * per_set - 1, None) == 3
+    assert lib.dd_prepare_shared(ctypes.byref(ok), 3, one, one, None, 3 * per_set, None) == 3
+    for fn in (lib.dd_fwd_shared, lib.dd_bwd_input_shared):
+        assert fn(ctypes.byref(ok), 0, one, blk, 8 * per_set, one, None) == 1
+        assert fn(ctypes.byref(ok), 9, one, blk, 9 * per_set, one, None) == 2
+        assert fn(ctypes.byref(ok), 3, one, blk, 3 * per_set - 1, one, None) == 3   # a block for fewer sets
+        assert fn(ctypes.byref(ok), 3, one, ctypes.c_void_p(520), 3 * per_set, one, None) == 3
+        assert fn(ctypes.byref(ok), 3, None, blk, 3 * per_set, one, None) == 1
+        assert fn(ctypes.byref(ok), 3, one, blk, 3 * per_set, None, None) == 1
+        # shapes and types the matrix-core kernels do not cover
+        for bad in (_layer(T=8, M=768, N=768, K=8, dtype=0), _layer(T=8, M=100, N=768, K=8, dtype=1)):
+            assert fn(ctypes.byref(bad), 3, one, blk, 1 << 30, one, None) == 2
+        # no tokens: nothing to do
+        assert fn(ctypes.byref(_layer(T=0, M=768, N=768, K=8, dtype=1)), 3, None, blk, 3 * per_set, None, None) == 0
+    bad = _layer(T=8, M=768, N=768, K=8, dtype=0)
+    assert lib.dd_prepare_shared(ctypes.byref(bad), 3, one, one, blk, 1 << 30, None) == 2
+
+
 def test_diagheur_rules(lib):
     one = ctypes.c_void_p(256)
     l = _layer(M=768, N=768, K=77)
