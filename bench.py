@@ -251,6 +251,29 @@ def main():
                  "paper_context": "paper reports 3.13x inference / 1.59x training speedup at 90 % sparsity, "
                                   "ViT-Base end to end, on an A100 (abstract, Sec. 4.2.3): another machine"}
 
+    # the same step replayed from a HIP graph (one graph holds one step per buffer set): what is left of the step
+    # time once the launches cost the host nothing; reported beside the contract's figure, not as it
+    try:
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for s_ in range(S):
+                    step(s_)
+        torch.cuda.synchronize()
+        reps = max(3, args.steps // S)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        breakdown["us_step_replayed_from_graph"] = (time.perf_counter() - t0) * 1e6 / (reps * S)
+        del graph
+    except Exception as exc:  # reported, never fatal: the contract's figures above do not depend on it
+        breakdown["us_step_replayed_from_graph"] = None
+        breakdown["graph_error"] = repr(exc)[:200]
+
     # the differentiable selection path (Sec. 3.2, Eq. 4-5), outside the timed step: launch-bound helpers
     d_V = d_val.clone()
     at = dd.dd_soft_topk(d_scores, K, 1.0)
