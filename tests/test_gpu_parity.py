@@ -260,6 +260,26 @@ def test_vitb_attention_projection_full(algo):
     check_against_oracle(offsets, values, X, dY, "bf16", ALGOS[algo])
 
 
+def test_vitb_attention_projection_full_as_benchmarked():
+    """The launch configuration bench.py times: offsets from the selection kernel, operands prepared once, both
+    products on them, the weight gradient by itself; 12608 tokens, every element."""
+    layer = synth.WORKLOADS["vitb_attn_proj"][0]
+    _, values, X, dY = synth.layer_inputs(layer, seed=2506)
+    scores = synth.draw_scores(1, layer.D, seed=2506)
+    M, N, K = layer.in_features, layer.out_features, layer.K
+    d_off = dd.dd_select_diagonals(torch.from_numpy(scores).cuda(), K)
+    offsets = orc.select(scores, K)[0]
+    assert np.array_equal(d_off[0].cpu().numpy(), offsets)
+    d_val, d_X, d_dY = to_dev(values, "bf16"), to_dev(X, "bf16"), to_dev(dY, "bf16")
+    prepared = dd.dd_prepare(d_off[0], d_val, M, N)
+    Y = dd.dd_fwd(d_X, None, None, N, prepared=prepared)
+    dX = dd.dd_bwd_input(d_dY, None, None, M, prepared=prepared)
+    dV = dd.dd_bwd_weight(d_X, d_dY, d_off[0])
+    assert rel_err(to_host(Y), orc.fwd(X, offsets, values, N)) <= TOL["bf16"]
+    assert rel_err(to_host(dX), orc.bwd_input(dY, offsets, values, M)) <= TOL["bf16"]
+    assert rel_err(to_host(dV), orc.bwd_weight(X, dY, offsets)) <= TOL_DV
+
+
 def _sampled_check(layer, seed, algo, n_rows=48, n_entries=256):
     offsets, values, X, dY = synth.layer_inputs(layer, seed)
     M, N = layer.in_features, layer.out_features
