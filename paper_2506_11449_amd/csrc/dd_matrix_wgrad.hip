@@ -366,6 +366,8 @@ __global__ __launch_bounds__(kWgT, kWgPerCu) void wgrad_mm_kernel(int T, int D, 
 // dV[k][p] = sum over the chunks of partial[chunk][rep(k)][p], rep(k) = first diagonal with k's offset.  The
 // chunks are cut into four runs that four groups of threads add up side by side, each in chunk order; the four
 // sums are then added in run order: a fixed order, so the result is the same on every call.
+// Repeated offsets are rare, so the first eight partial sums of diagonal k itself are requested before the search
+// for rep(k) (whose loads and barriers they then overlap) and fetched again only if k turns out not to be first.
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(int D, int L, int K, int splits,
                                                            const int *__restrict__ offsets,
                                                            const float *__restrict__ partial,
@@ -374,6 +376,20 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(int D, int L, int K, 
     __shared__ int rep_s;
     __shared__ f32x4 run_s[3][64];
     const int k = blockIdx.y;
+    const int run = threadIdx.x >> 6, g = threadIdx.x & 63;
+    const int p = blockIdx.x * 256 + g * 4;  // L is a multiple of 64
+    const int per_run = (splits + 3) / 4;
+    const int s_begin = min(run * per_run, splits), s_end = min(s_begin + per_run, splits);
+    const size_t stride = size_t(K) * L;
+    const bool active = p < L;
+    const bool first_batch = active && s_begin + 8 <= s_end;
+    f32x4 v[8];
+    if (first_batch) {
+        const float *src = partial + (size_t(s_begin) * K + k) * L + p;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x4 *>(src + u * stride);
+    }
+
     if (threadIdx.x == 0) rep_s = k;
     __syncthreads();
     const int mine = canonical_offset(offsets[k], D);
@@ -381,17 +397,22 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(int D, int L, int K, 
         if (canonical_offset(offsets[j], D) == mine) atomicMin(&rep_s, j);
     __syncthreads();
     const int rep = rep_s;
-    const int run = threadIdx.x >> 6, g = threadIdx.x & 63;
-    const int p = blockIdx.x * 256 + g * 4;  // L is a multiple of 64
-    const int per_run = (splits + 3) / 4;
-    const int s_begin = min(run * per_run, splits), s_end = min(s_begin + per_run, splits);
+
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    if (p < L) {
-        const size_t stride = size_t(K) * L;
+    if (active) {
         const float *src = partial + (size_t(s_begin) * K + rep) * L + p;
         int s = s_begin;
+        if (first_batch) {
+            if (rep != k) {  // uniform over the workgroup
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x4 *>(src + u * stride);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += v[u];
+            src += 8 * stride;
+            s += 8;
+        }
         for (; s + 8 <= s_end; s += 8) {  // eight loads in flight
-            f32x4 v[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x4 *>(src + u * stride);
 #pragma unroll
@@ -405,7 +426,7 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(int D, int L, int K, 
     }
     if (run > 0) run_s[run - 1][g] = acc;
     __syncthreads();
-    if (run == 0 && p < L) {
+    if (run == 0 && active) {
         acc = ((acc + run_s[0][g]) + run_s[1][g]) + run_s[2][g];
         *reinterpret_cast<f32x4 *>(dV + size_t(k) * L + p) = acc;
     }
