@@ -26,7 +26,11 @@
  *   - Errors are reported by the return value; nothing is thrown and nothing aborts.
  *     DD_ERR_INVALID_ARG: null pointer, tokens < 0, features < 1, K < 1, K > D, unknown
  *     dtype or algo.  DD_ERR_WORKSPACE: ws_bytes below dd_workspace_bytes or ws misaligned.
- *     DD_ERR_UNSUPPORTED: a size the kernels do not cover (stated per function).
+ *     DD_ERR_UNSUPPORTED: a size the kernels do not cover (stated per function); for the three
+ *     products: max(M, N) > 65535, or DD_ALGO_MATRIX / DD_ALGO_PREPARED forced where the matrix-core
+ *     kernels do not apply.  They cover bf16 storage, 16-byte aligned matrices and M, N both multiples
+ *     of 128 (dd_bwd_weight: both multiples of 192, or both of 128), max(M, N) <= 8192; DD_ALGO_AUTO
+ *     takes them there when K / max(M, N) >= 1/48 and the vector kernels everywhere else.
  *     DD_ERR_HIP: the launch itself failed.
  *   - tokens == 0 is legal: fwd / bwd_input return DD_OK without a launch; bwd_weight
  *     writes zeros.
@@ -56,7 +60,7 @@ typedef enum { DD_F32 = 0, DD_BF16 = 1 } dd_dtype;
 typedef enum {
     DD_ALGO_AUTO = 0,
     DD_ALGO_VECTOR = 1, /* direct diagonal kernels on the vector ALUs: work ~ tokens*K*L   */
-    DD_ALGO_MATRIX = 2, /* W tiles rebuilt on chip and multiplied on the matrix cores       */
+    DD_ALGO_MATRIX = 2, /* the diagonals rebuilt as a dense operand in scratch, product on the matrix cores */
     DD_ALGO_PREPARED = 3 /* as DD_ALGO_MATRIX, with the dense operands already built by dd_prepare */
 } dd_algo;
 
