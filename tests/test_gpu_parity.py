@@ -280,6 +280,14 @@ def test_vitb_attention_projection_full_as_benchmarked():
     assert rel_err(to_host(dV), orc.bwd_weight(X, dY, offsets)) <= TOL_DV
 
 
+@pytest.mark.parametrize("algo", ["vector", "matrix"])
+def test_many_tokens_sampled(algo):
+    """300001 tokens through a narrow layer: thousands of tiles per product, token counts far past any 16-bit grid
+    limit, a ragged last tile; sampled token rows and sampled gradient entries against the oracle."""
+    layer = synth.Layer("narrow", 300001, 128, 256, 26, "bf16")
+    _sampled_check(layer, 7, ALGOS[algo], n_rows=64, n_entries=128)
+
+
 def _sampled_check(layer, seed, algo, n_rows=48, n_entries=256):
     offsets, values, X, dY = synth.layer_inputs(layer, seed)
     M, N = layer.in_features, layer.out_features
