@@ -118,6 +118,19 @@ dd_status dd_prepare(const dd_layer *layer, const int32_t *offsets, const void *
                      size_t prepared_bytes, void *hip_stream);
 
 /*
+ * dd_select_diagonals for one score vector followed by dd_prepare on the diagonals it chose, as one call (one
+ * launch for layers of up to 1024 candidate diagonals, where the launches are most of what the two steps cost;
+ * two launches beyond).  The results are those of the two calls, bit for bit.
+ *   scores      [D]      fp32   in    importance of the D = max(M, N) candidate diagonals (Sec. 3.2 Eq. 4)
+ *   values      [K x L]  dtype  in    values[k] belongs to the k-th chosen diagonal in ascending order of offset
+ *   offsets_out [K]      int32  out   the chosen offsets, ascending (for dd_bwd_weight and the caller)
+ *   prepared                    out   as for dd_prepare
+ * Errors as for dd_prepare.
+ */
+dd_status dd_select_prepare(const dd_layer *layer, const float *scores, const void *values, int32_t *offsets_out,
+                            void *prepared, size_t prepared_bytes, void *hip_stream);
+
+/*
  * Backward product with respect to the input, dX = dY . W_K^T, over the same diagonals
  * (Sec. 3.3: the transposed matrix is again diagonal-sparse with the same starts, Appendix A).
  *   dY [tokens x N] in,  dX [tokens x M] out;  offsets / values exactly as given to dd_fwd.

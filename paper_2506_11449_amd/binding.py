@@ -16,7 +16,7 @@ DD_ALGO_AUTO, DD_ALGO_VECTOR, DD_ALGO_MATRIX, DD_ALGO_PREPARED = 0, 1, 2, 3
 DD_OP_FWD, DD_OP_BWD_INPUT, DD_OP_BWD_WEIGHT, DD_OP_SELECT, DD_OP_SCALE_VALUES_BWD, DD_OP_PREPARE = 0, 1, 2, 3, 4, 5
 DD_OP_DIAGHEUR = 6
 
-EXPORTS = ("dd_workspace_bytes", "dd_fwd", "dd_prepare", "dd_prepare_shared", "dd_fwd_shared", "dd_bwd_input_shared",
+EXPORTS = ("dd_workspace_bytes", "dd_fwd", "dd_prepare", "dd_select_prepare", "dd_prepare_shared", "dd_fwd_shared", "dd_bwd_input_shared",
            "dd_bwd_input", "dd_bwd_weight", "dd_select_diagonals",
            "dd_soft_topk", "dd_soft_topk_bwd", "dd_scale_values", "dd_scale_values_bwd", "dd_diag_magnitude",
            "dd_diagheur_update", "dd_status_string")
@@ -50,6 +50,7 @@ def load_library():
     lib.dd_workspace_bytes.restype = sz
     lib.dd_fwd.argtypes = [lp, vp, vp, vp, vp, vp, sz, vp]
     lib.dd_prepare.argtypes = [lp, vp, vp, vp, sz, vp]
+    lib.dd_select_prepare.argtypes = [lp, vp, vp, vp, vp, sz, vp]
     lib.dd_prepare_shared.argtypes = [lp, i32, vp, vp, vp, sz, vp]
     lib.dd_fwd_shared.argtypes = [lp, i32, vp, vp, sz, vp, vp]
     lib.dd_bwd_input_shared.argtypes = [lp, i32, vp, vp, sz, vp, vp]
@@ -163,6 +164,25 @@ def dd_prepare(offsets, values, in_features, out_features, prepared=None, stream
         raise ValueError("prepared block belongs to another layer")
     _check(load_library().dd_prepare(ref, _ptr(offsets), _ptr(values), _ptr(prepared.buf), prepared.buf.numel(), _stream(stream)))
     return prepared
+
+
+def dd_select_prepare(scores, values, in_features, out_features, offsets_out=None, prepared=None, stream=None):
+    """dd_select_diagonals on one score vector [D] and dd_prepare on its result, one call: (offsets [K], prepared)."""
+    M, N, K = int(in_features), int(out_features), values.shape[0]
+    D = max(M, N)
+    _, ref, need = _plan(DD_OP_PREPARE, 0, M, N, K, values.dtype, DD_ALGO_PREPARED)
+    _dev(scores, torch.float32, (D,), "scores")
+    _dev(values, values.dtype, (K, min(M, N)), "values")
+    if offsets_out is None:
+        offsets_out = torch.empty((K,), dtype=torch.int32, device=values.device)
+    _dev(offsets_out, torch.int32, (K,), "offsets_out")
+    if prepared is None:
+        prepared = Prepared(torch.empty(max(need, 1), dtype=torch.uint8, device=values.device), M, N, K, values.dtype)
+    if (prepared.in_features, prepared.out_features, prepared.K, prepared.dtype) != (M, N, K, values.dtype):
+        raise ValueError("prepared block belongs to another layer")
+    _check(load_library().dd_select_prepare(ref, _ptr(scores), _ptr(values), _ptr(offsets_out), _ptr(prepared.buf),
+                                            prepared.buf.numel(), _stream(stream)))
+    return offsets_out, prepared
 
 
 class PreparedShared:

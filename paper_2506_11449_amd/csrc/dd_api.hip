@@ -165,6 +165,29 @@ dd_status dd_prepare(const dd_layer *layer, const int32_t *offsets, const void *
     return e == hipSuccess ? DD_OK : DD_ERR_HIP;
 }
 
+dd_status dd_select_prepare(const dd_layer *layer, const float *scores, const void *values, int32_t *offsets_out,
+                            void *prepared, size_t prepared_bytes_given, void *hip_stream)
+{
+    Shape s;
+    if (dd_status st = check_layer(layer, &s)) return st;
+    if (!scores || !values || !offsets_out) return DD_ERR_INVALID_ARG;
+    if (layer->algo == DD_ALGO_VECTOR) return DD_ERR_UNSUPPORTED;
+    if (!dd::product_matrix_supported(1, s.D, s.L, layer->dtype == DD_BF16)) return DD_ERR_UNSUPPORTED;
+    if (dd_status st = check_ws(prepared, prepared_bytes_given, prepared_bytes(s))) return st;
+    unsigned char *first = static_cast<unsigned char *>(prepared);
+    unsigned char *second = first + dd::product_matrix_ws_bytes(s.D, s.L);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t e;
+    if (dd::select_prepare_fused(s.D, s.L, layer->K)) {
+        e = dd::launch_select_prepare(s.D, s.L, layer->K, s.expanding, scores, values, offsets_out, first, second, stream);
+    } else {  // larger layers: the two steps one after the other, same results
+        e = dd::launch_select(1, s.D, layer->K, scores, offsets_out, stream);
+        if (e == hipSuccess)
+            e = dd::launch_prepare_matrix(s.D, s.L, layer->K, 1, s.expanding, offsets_out, values, first, second, stream);
+    }
+    return e == hipSuccess ? DD_OK : DD_ERR_HIP;
+}
+
 dd_status dd_prepare_shared(const dd_layer *layer, int32_t n_sets, const int32_t *offsets, const void *values,
                             void *prepared, size_t prepared_bytes_given, void *hip_stream)
 {

@@ -51,6 +51,12 @@ hipError_t launch_product_matrix(const ProductArgs &a, hipStream_t stream);
 hipError_t launch_prepare_matrix(int D, int L, int K, int sets, bool expanding, const int32_t *offsets,
                                  const void *values, void *forward_operand, void *backward_operand,
                                  hipStream_t stream);
+// Selection of the K diagonals from `scores` [D] and both dense operands from them in one launch (small layers
+// only: ask select_prepare_fused first).  offsets_out [K] receives the chosen offsets, ascending.
+bool select_prepare_fused(int D, int L, int K);
+hipError_t launch_select_prepare(int D, int L, int K, bool expanding, const float *scores, const void *values,
+                                 int32_t *offsets_out, void *forward_operand, void *backward_operand,
+                                 hipStream_t stream);
 size_t weight_grad_vector_ws_bytes(int64_t T, int D, int L, int K, bool bf16);
 hipError_t launch_weight_grad_vector(const WeightGradArgs &a, hipStream_t stream);
 // bf16 dot-product kernel of the vector family (feature counts multiples of 8, long side <= 2304)

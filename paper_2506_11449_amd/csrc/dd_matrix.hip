@@ -23,6 +23,7 @@
 //   LDS once and stored with full-width row segments.
 #include "dd_common.h"
 #include "dd_launch.h"
+#include "dd_select_block.h"
 
 // Tuning hooks for experiments (normal builds leave them alone): waves per workgroup, and
 // -DDD_MM_FORCE=BM,BN,NW to pin one tile shape.
@@ -43,6 +44,7 @@ constexpr int kChunksPerRow = kBK / 8;  // 16-byte chunks per LDS row
 constexpr int kRowBytes = kBK * 2;
 constexpr int kXcds = 8;
 constexpr int kRing = 3;         // LDS stages of the token operand
+constexpr int kFusedRows = 3;    // operand rows per workgroup of select_materialize_kernel
 
 // position of 16-byte chunk `chunk` (0..7) inside its 128-byte row
 __device__ __forceinline__ int swizzle_key(int row) { return (row >> 1) & 7; }
@@ -110,6 +112,69 @@ __global__ __launch_bounds__(256) void materialize_kernel(int D, int L, int K, i
             v[e] = uint32_t(f32_to_bf16(row[c8 * 8 + 2 * e])) | (uint32_t(f32_to_bf16(row[c8 * 8 + 2 * e + 1])) << 16);
         *reinterpret_cast<u32x4 *>(Wf + fragment_index(r + set * place.col_step, c8 * 8 + set * place.k_step,
                                                        place.kd_total)) = v;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Selection and step 1 in one launch, for layers small enough that the launches themselves are what the two
+// steps cost: every workgroup repeats the selection of the K diagonals (Sec. 3.2 Eq. 4) for itself, keeps the
+// chosen offsets in LDS, and then builds ROWS rows of the two operands from them; workgroup 0 also writes the
+// offsets out.  Rows [0, D) are rows of the masked-gather operand, rows [D, D + L) rows of the gather operand.
+// The selection never returns an offset twice, so no two diagonals meet in one entry and the operands come out
+// bit for bit as materialize_kernel builds them.
+// LDS: keys [D] | chosen offsets [K] | ROWS rows of D floats.
+// ---------------------------------------------------------------------------------------------
+template <int ROWS>
+__global__ __launch_bounds__(kSelectThreads) void select_materialize_kernel(int D, int L, int K,
+                                                                             const float *__restrict__ scores,
+                                                                             const uint16_t *__restrict__ values,
+                                                                             int *__restrict__ offsets_out,
+                                                                             uint16_t *__restrict__ Wf_masked,
+                                                                             uint16_t *__restrict__ Wf_gather)
+{
+    extern __shared__ uint32_t lds_words[];
+    uint32_t *keys = lds_words;
+    int *chosen = reinterpret_cast<int *>(lds_words + D);
+    float *rows = reinterpret_cast<float *>(lds_words + D + K);
+    for (int i = threadIdx.x; i < ROWS * D; i += kSelectThreads) rows[i] = 0.f;
+    select_topk_block<true>(D, K, scores, keys, chosen);
+    __syncthreads();
+    if (blockIdx.x == 0)
+        for (int k = threadIdx.x; k < K; k += kSelectThreads) offsets_out[k] = chosen[k];
+    const int r0 = blockIdx.x * ROWS;
+    for (int k = threadIdx.x; k < K; k += kSelectThreads) {
+        const int o = chosen[k];  // already in [0, D)
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) {
+            const int r = r0 + j;
+            if (r < D) {  // masked gather, row q = r:  w[p] = v_k[p] where (q - o_k) mod D = p < L
+                int pp = r - o;
+                if (pp < 0) pp += D;
+                if (pp < L) rows[j * D + pp] = bf16_to_f32(values[size_t(k) * L + pp]);
+            } else if (r < D + L) {  // gather, row p = r - D:  w[q] = v_k[p] where q = (p + o_k) mod D
+                int q = r - D + o;
+                if (q >= D) q -= D;
+                rows[j * D + q] = bf16_to_f32(values[size_t(k) * L + (r - D)]);
+            }
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) {
+        const int r = r0 + j;
+        if (r >= D + L) break;
+        const bool long_major = r < D;
+        const int KD = long_major ? L : D;
+        uint16_t *Wf = long_major ? Wf_masked : Wf_gather;
+        const int out_row = long_major ? r : r - D;
+        for (int c8 = threadIdx.x; c8 < KD / 8; c8 += kSelectThreads) {
+            u32x4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                v[e] = uint32_t(f32_to_bf16(rows[j * D + c8 * 8 + 2 * e])) |
+                       (uint32_t(f32_to_bf16(rows[j * D + c8 * 8 + 2 * e + 1])) << 16);
+            *reinterpret_cast<u32x4 *>(Wf + fragment_index(out_row, c8 * 8, KD)) = v;
+        }
     }
 }
 
@@ -624,6 +689,25 @@ hipError_t launch_prepare_matrix(int D, int L, int K, int sets, bool expanding, 
                        static_cast<uint16_t *>(expanding ? forward_operand : backward_operand),
                        static_cast<uint16_t *>(expanding ? backward_operand : forward_operand),
                        expanding ? side_by_side : stacked, expanding ? stacked : side_by_side);
+    return hipGetLastError();
+}
+
+bool select_prepare_fused(int D, int L, int K)
+{
+    // pays while a handful of resident workgroups per CU cover all rows at once; beyond that the repeated
+    // selections cost more than the launch they save
+    return D <= 1024 && size_t(D + K + kFusedRows * D) * 4 <= 48 * 1024;
+}
+
+hipError_t launch_select_prepare(int D, int L, int K, bool expanding, const float *scores, const void *values,
+                                 int32_t *offsets_out, void *forward_operand, void *backward_operand,
+                                 hipStream_t stream)
+{
+    const size_t lds = size_t(D + K + kFusedRows * D) * 4;
+    hipLaunchKernelGGL(select_materialize_kernel<kFusedRows>, dim3((D + L + kFusedRows - 1) / kFusedRows),
+                       dim3(kSelectThreads), lds, stream, D, L, K, scores, static_cast<const uint16_t *>(values),
+                       offsets_out, static_cast<uint16_t *>(expanding ? forward_operand : backward_operand),
+                       static_cast<uint16_t *>(expanding ? backward_operand : forward_operand));
     return hipGetLastError();
 }
 

@@ -1,117 +1,19 @@
 // Hard TopK re-selection of active diagonals (Sec. 3.2, Eq. 4): which K of the D importance
 // scores are kept.  One workgroup per score vector, integer comparisons only, so the result
 // is the same on every run and on every device.
-//
-// Method: scores are mapped to 32-bit keys whose unsigned order is the required total order
-// (NaN lowest, -0 == +0) and parked in LDS.  A four-pass byte-wise radix search finds the K-th
-// largest key tau and how many of the keys equal to tau still belong to the selection (the
-// lowest-indexed ones); each pass is one LDS histogram plus a suffix scan done by a single wave
-// with lane shuffles.  A last pass walks the indices in ascending order and compacts the chosen
-// ones with a workgroup prefix sum, which also yields them already sorted by index.
+// The method itself is in dd_select_block.h.
 #include "dd_common.h"
 #include "dd_launch.h"
+#include "dd_select_block.h"
 
 namespace dd {
-
-constexpr int kSelectThreads = 256;
-constexpr int kSelectLdsKeys = 16384;  // score vectors up to this length keep their keys in LDS
-
-__device__ __forceinline__ uint32_t score_key(float s)
-{
-    if (s != s) return 0u;             // NaN: below every number
-    uint32_t u = __float_as_uint(s + 0.0f);  // -0 + 0 = +0
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-// inclusive prefix sum over the 64 lanes of a wave
-__device__ __forceinline__ unsigned wave_inclusive_scan(unsigned v, int lane)
-{
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const unsigned up = __shfl_up(v, d, 64);
-        if (lane >= d) v += up;
-    }
-    return v;
-}
 
 template <bool KEYS_IN_LDS>
 __global__ __launch_bounds__(kSelectThreads) void select_topk_kernel(
     int D, int K, const float *__restrict__ scores, int *__restrict__ out)
 {
     extern __shared__ uint32_t s_keys[];  // [D] when KEYS_IN_LDS
-    __shared__ unsigned hist[256];
-    __shared__ unsigned s_prefix, s_remaining;
-    __shared__ unsigned wave_gt[4], wave_eq[4];
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const float *row = scores + size_t(blockIdx.x) * D;
-    int *dst = out + size_t(blockIdx.x) * K;
-    auto key_at = [&](int i) -> uint32_t { return KEYS_IN_LDS ? s_keys[i] : score_key(row[i]); };
-
-    if (KEYS_IN_LDS)
-        for (int i = tid; i < D; i += kSelectThreads) s_keys[i] = score_key(row[i]);
-    if (tid == 0) { s_prefix = 0u; s_remaining = unsigned(K); }
-    unsigned mask = 0u;
-    for (int shift = 24; shift >= 0; shift -= 8) {
-        hist[tid] = 0u;
-        __syncthreads();
-        const unsigned prefix = s_prefix, remaining = s_remaining;
-        for (int i = tid; i < D; i += kSelectThreads) {
-            const uint32_t key = key_at(i);
-            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
-        }
-        __syncthreads();
-        if (wave == 0) {
-            // lane l owns bins 255-4l .. 252-4l (descending); find the bin where the running count of
-            // larger-or-equal keys first reaches `remaining`
-            unsigned h[4], mine = 0u;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) { h[j] = hist[255 - 4 * lane - j]; mine += h[j]; }
-            const unsigned incl = wave_inclusive_scan(mine, lane);
-            unsigned above = incl - mine;  // keys in bins larger than this lane's
-            if (above < remaining && incl >= remaining) {  // exactly one lane
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if (above + h[j] >= remaining) {
-                        s_remaining = remaining - above;  // still to take inside the chosen bin
-                        s_prefix = prefix | (unsigned(255 - 4 * lane - j) << shift);
-                        break;
-                    }
-                    above += h[j];
-                }
-            }
-        }
-        mask |= 255u << shift;
-        __syncthreads();
-    }
-    const uint32_t tau = s_prefix;          // the K-th largest key
-    const unsigned take_eq = s_remaining;   // how many keys equal to tau are selected (>= 1)
-
-    // contiguous chunk of indices per thread, so that a prefix sum keeps ascending order
-    const int chunk = (D + kSelectThreads - 1) / kSelectThreads;
-    const int lo = min(tid * chunk, D), hi = min(lo + chunk, D);
-    unsigned n_gt = 0u, n_eq = 0u;
-    for (int i = lo; i < hi; ++i) {
-        const uint32_t key = key_at(i);
-        n_gt += key > tau;
-        n_eq += key == tau;
-    }
-    const unsigned incl_gt = wave_inclusive_scan(n_gt, lane), incl_eq = wave_inclusive_scan(n_eq, lane);
-    if (lane == 63) { wave_gt[wave] = incl_gt; wave_eq[wave] = incl_eq; }
-    __syncthreads();
-    unsigned base_gt = 0u, base_eq = 0u;
-    for (int w = 0; w < wave; ++w) { base_gt += wave_gt[w]; base_eq += wave_eq[w]; }
-    unsigned eq_rank = base_eq + incl_eq - n_eq;                       // equal keys before this chunk
-    unsigned pos = (base_gt + incl_gt - n_gt) + min(eq_rank, take_eq);  // selected before this chunk
-    for (int i = lo; i < hi; ++i) {
-        const uint32_t key = key_at(i);
-        if (key > tau) {
-            dst[pos++] = i;
-        } else if (key == tau) {
-            if (eq_rank < take_eq) dst[pos++] = i;
-            ++eq_rank;
-        }
-    }
+    select_topk_block<KEYS_IN_LDS>(D, K, scores + size_t(blockIdx.x) * D, s_keys, out + size_t(blockIdx.x) * K);
 }
 
 hipError_t launch_select(int batch, int D, int K, const float *scores, int *out, hipStream_t stream)

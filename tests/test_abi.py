@@ -111,6 +111,22 @@ def test_prepare_rules(lib):
     assert lib.dd_bwd_input(ctypes.byref(ok), one, None, None, one, ctypes.c_void_p(512), need - 1, None) == 3
 
 
+def test_select_prepare_rules(lib):
+    one = ctypes.c_void_p(256)
+    blk = ctypes.c_void_p(512)
+    ok = _layer(T=0, M=768, N=768, K=30, dtype=1)
+    need = lib.dd_workspace_bytes(binding.DD_OP_PREPARE, ctypes.byref(ok), 0)
+    assert lib.dd_select_prepare(ctypes.byref(ok), None, one, one, blk, need, None) == 1
+    assert lib.dd_select_prepare(ctypes.byref(ok), one, None, one, blk, need, None) == 1
+    assert lib.dd_select_prepare(ctypes.byref(ok), one, one, None, blk, need, None) == 1
+    assert lib.dd_select_prepare(ctypes.byref(ok), one, one, one, None, need, None) == 3
+    assert lib.dd_select_prepare(ctypes.byref(ok), one, one, one, blk, need - 1, None) == 3
+    for bad in (_layer(M=768, N=768, K=8, dtype=0), _layer(M=100, N=768, K=8, dtype=1),
+                _layer(M=768, N=768, K=8, dtype=1, algo=binding.DD_ALGO_VECTOR)):
+        assert lib.dd_select_prepare(ctypes.byref(bad), one, one, one, blk, 1 << 30, None) == 2
+    assert lib.dd_select_prepare(ctypes.byref(_layer(M=768, N=768, K=800, dtype=1)), one, one, one, blk, need, None) == 1
+
+
 def test_shared_input_rules(lib):
     one = ctypes.c_void_p(256)
     blk = ctypes.c_void_p(512)

@@ -137,6 +137,34 @@ def test_prepared_products(M, N, K, T):
         assert rel_err(to_host(dV), orc.bwd_weight(X, dY, offsets)) <= TOL_DV
 
 
+@pytest.mark.parametrize("M,N,K", [(768, 768, 77), (128, 384, 40), (384, 128, 30), (1024, 1024, 51), (128, 128, 128),
+                                   (256, 256, 1), (768, 3072, 307), (2048, 512, 60)])
+def test_select_and_prepare_in_one_call(M, N, K):
+    """dd_select_prepare against the oracle's selection and, bit for bit, against dd_prepare on those offsets; layers
+    of up to 1024 candidates take one launch, the last two cases two.  Scores carry ties, a NaN and signed zeros."""
+    D, L = max(M, N), min(M, N)
+    rng = np.random.default_rng(M * 7 + N + K)
+    scores = np.round(rng.standard_normal(D) * 4).astype(np.float32) / 4  # heavily tied
+    scores[D // 3] = np.nan
+    scores[D // 2], scores[D // 2 + 1] = 0.0, -0.0
+    values = synth.round_to_bf16((rng.standard_normal((K, L)) * 0.02).astype(np.float32))
+    X = synth.round_to_bf16(rng.standard_normal((150, M)).astype(np.float32))
+    d_scores, d_val = torch.from_numpy(scores).cuda(), to_dev(values, "bf16")
+    offsets = orc.select(scores, K)[0]
+    for round_ in range(2):  # the second time into the blocks of the first
+        if round_ == 0:
+            d_off, prepared = dd.dd_select_prepare(d_scores, d_val, M, N)
+        else:
+            d_off.fill_(-1)
+            prepared.buf.fill_(0xAB)
+            dd.dd_select_prepare(d_scores, d_val, M, N, offsets_out=d_off, prepared=prepared)
+        assert np.array_equal(d_off.cpu().numpy(), offsets)
+        separate = dd.dd_prepare(torch.from_numpy(offsets).cuda(), d_val, M, N)
+        assert torch.equal(prepared.buf, separate.buf)
+    Y = dd.dd_fwd(to_dev(X, "bf16"), None, None, N, prepared=prepared)
+    assert rel_err(to_host(Y), orc.fwd(X, offsets, values, N)) <= TOL["bf16"]
+
+
 def test_prepared_refuses_what_the_matrix_cores_do_not_cover():
     off = torch.zeros(4, dtype=torch.int32, device="cuda")
     for M, N, dtype in ((100, 768, torch.bfloat16), (768, 768, torch.float32)):
