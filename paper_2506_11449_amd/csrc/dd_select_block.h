@@ -22,15 +22,22 @@ __device__ __forceinline__ uint32_t score_key(float s)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// inclusive prefix sum over the 64 lanes of a wave
+// Inclusive prefix sum over the 64 lanes of a wave, without a trip through LDS: four shift-and-add steps inside
+// each row of 16 lanes (DPP row_shr, lanes shifted in from outside the row read 0), then the totals of the rows
+// before a lane's own row, read from lanes 15, 31 and 47.
 __device__ __forceinline__ unsigned wave_inclusive_scan(unsigned v, int lane)
 {
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const unsigned up = __shfl_up(v, d, 64);
-        if (lane >= d) v += up;
-    }
-    return v;
+#define DD_ROW_SHR(n_) unsigned(__builtin_amdgcn_update_dpp(0, int(v), 0x110 + (n_), 0xf, 0xf, true))
+    v += DD_ROW_SHR(1);
+    v += DD_ROW_SHR(2);
+    v += DD_ROW_SHR(4);
+    v += DD_ROW_SHR(8);
+#undef DD_ROW_SHR
+    const unsigned r0 = unsigned(__builtin_amdgcn_readlane(int(v), 15));
+    const unsigned r1 = unsigned(__builtin_amdgcn_readlane(int(v), 31));
+    const unsigned r2 = unsigned(__builtin_amdgcn_readlane(int(v), 47));
+    const int row = lane >> 4;
+    return v + (row >= 1 ? r0 : 0u) + (row >= 2 ? r1 : 0u) + (row >= 3 ? r2 : 0u);
 }
 
 // The selection for one score vector `row` by one workgroup of kSelectThreads threads: the K chosen indices go to
