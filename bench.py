@@ -352,7 +352,7 @@ def main():
         "config": {"workload": f"ViT-Base attention projection: {M}->{N}, 90% sparse (K={K} diagonals), "
                                f"tokens={T}, bf16 storage, fp32 accumulate" if args.workload == "vitb_attn_proj"
                    else layer.name,
-                   "step": ("dd_select_diagonals + dd_prepare + dd_fwd + dd_bwd_input + dd_bwd_weight" if use_prepare
+                   "step": ("dd_select_prepare (dd_select_diagonals and dd_prepare as one call) + dd_fwd + dd_bwd_input + dd_bwd_weight" if use_prepare
                             else "dd_select_diagonals + dd_fwd + dd_bwd_input + dd_bwd_weight"),
                    "offsets": "uniform" if args.offset_bands == 0 else f"{args.offset_bands} runs of adjacent diagonals",
                    "algo": args.algo, "buffer_sets": S, "tokens": T, "in_features": M, "out_features": N, "K": K},
