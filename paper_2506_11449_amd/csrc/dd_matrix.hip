@@ -202,27 +202,35 @@ struct MmTile {
 
 // Result tile (tm, tn), held row by row in LDS, to the stack of [T x c_cols] matrices C: 16-byte pieces, full-width
 // row segments.  A tile of BN <= 256 columns reaches into at most three matrices of 128 or more columns.
+// One 16-byte piece per thread: piece number idx of the tile whose first column is column first_col of matrix
+// first_matrix of the stack.
+template <int BM, int BN>
+__device__ __forceinline__ void store_tile_piece(uint16_t *__restrict__ C, const unsigned char *tile, int tile_stride,
+                                                 int tm, int first_matrix, int first_col, int T, int c_cols, int idx)
+{
+    constexpr int ROW_CHUNKS = BN / 8;
+    const int row = idx / ROW_CHUNKS, ch = idx % ROW_CHUNKS;
+    const int t = tm * BM + row;
+    int matrix = first_matrix, col = first_col + ch * 8;
+#pragma unroll
+    for (int hop = 0; hop < 2; ++hop)
+        if (col >= c_cols) {
+            col -= c_cols;
+            ++matrix;
+        }
+    if (row < BM && t < T)
+        *reinterpret_cast<u32x4 *>(C + (size_t(matrix) * T + t) * c_cols + col) =
+            *reinterpret_cast<const u32x4 *>(tile + row * tile_stride + ch * 16);
+}
+
 template <int BM, int BN, int THREADS>
 __device__ __forceinline__ void store_tile(uint16_t *__restrict__ C, const unsigned char *tile, int tile_stride, int tm,
                                            int tn, int T, int c_cols, int tid)
 {
-    constexpr int ROW_CHUNKS = BN / 8;
     const int first_matrix = (tn * BN) / c_cols;
     const int first_col = tn * BN - first_matrix * c_cols;
-    for (int idx = tid; idx < BM * ROW_CHUNKS; idx += THREADS) {
-        const int row = idx / ROW_CHUNKS, ch = idx % ROW_CHUNKS;
-        const int t = tm * BM + row;
-        int matrix = first_matrix, col = first_col + ch * 8;
-#pragma unroll
-        for (int hop = 0; hop < 2; ++hop)
-            if (col >= c_cols) {
-                col -= c_cols;
-                ++matrix;
-            }
-        if (t < T)
-            *reinterpret_cast<u32x4 *>(C + (size_t(matrix) * T + t) * c_cols + col) =
-                *reinterpret_cast<const u32x4 *>(tile + row * tile_stride + ch * 16);
-    }
+    for (int idx = tid; idx < BM * (BN / 8); idx += THREADS)
+        store_tile_piece<BM, BN>(C, tile, tile_stride, tm, first_matrix, first_col, T, c_cols, idx);
 }
 
 template <int BM, int BN, int NW>
@@ -417,8 +425,11 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
 // Step 2 for products with more tiles than CUs: one workgroup per CU walks a list of tiles, and the
 // software pipeline of mm_kernel runs through from tile to tile: while the last k-slices of a tile are
 // multiplied, the first slices of the next tile are already on their way (where mm_kernel re-reads the
-// last slice to keep its loop uniform), so a tile costs its main loop and the copy-out of its result, not
-// another fill of the pipeline.  The result tile has an LDS buffer of its own beside the ring.
+// last slice to keep its loop uniform), so a tile costs its main loop, not another fill of the pipeline.  The
+// copy-out of a tile's result is dealt out between the MFMAs of the next tile's first two slices: at the end of
+// a tile the accumulators are rounded into registers and cleared, during the next slice those registers go to an
+// LDS buffer of the result's own beside the ring, and during the slice after that the buffer leaves for memory
+// in full-width row segments.  Only the last tile of a workgroup is copied out with nothing to hide behind.
 // ---------------------------------------------------------------------------------------------
 template <int BM, int BN, int NW>
 __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, int KD, int a_cols, int c_cols,
@@ -570,25 +581,78 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
     // One k-slice.  Its requests (weight fragments of slice g_ + 1, token slice g_ + 4) go to addresses worked out
     // during the slice before, and the addresses for the slice after are worked out between its MFMAs, once the
     // requests that use the old ones are out: no address arithmetic stands between the barrier and the first MFMA.
-#define DD_SLICE(g_, wf_cur_, wf_next_, xg_)                                                            \
+#define DD_SLICE_X(g_, wf_cur_, wf_next_, xg_, e0_, e1_, e2_, e3_)                                       \
     {                                                                                                   \
         unsigned char *x_dstb = smem + (((g_) + 2) % kRing) * Tl::X_BYTES;                              \
         DD_STEP(wf_cur_, 0, xf0, xf1, g_, 1,                                                            \
                 if (b < 2) { _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a) {                       \
                     wf_next_[2 * b][a] = *reinterpret_cast<const bf16x8 *>(w_ptr[a] + (2 * b) * 512);   \
-                    wf_next_[2 * b + 1][a] = *reinterpret_cast<const bf16x8 *>(w_ptr[a] + (2 * b + 1) * 512); } }) \
+                    wf_next_[2 * b + 1][a] = *reinterpret_cast<const bf16x8 *>(w_ptr[a] + (2 * b + 1) * 512); } } \
+                e0_)                                                                                    \
         DD_STEP(wf_cur_, 1, xf1, xf0, g_, 2,                                                            \
                 if (b == 0) DD_ADVANCE(wc)                                                              \
-                if (b == 1) { _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a) w_ptr[a] = DD_W_AT(a); }) \
+                if (b == 1) { _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a) w_ptr[a] = DD_W_AT(a); } \
+                e1_)                                                                                    \
         DD_STEP(wf_cur_, 2, xf0, xf1, g_, 3,                                                            \
                 if (b < Tl::X_CHUNKS) { *reinterpret_cast<u32x4 *>(x_dstb + x_dst[b]) = xg_[b];         \
-                                        xg_[b] = *reinterpret_cast<const u32x4 *>(x_ptr[b]); })         \
+                                        xg_[b] = *reinterpret_cast<const u32x4 *>(x_ptr[b]); }          \
+                e2_)                                                                                    \
         DD_STEP(wf_cur_, 3, xf1, xf0, (g_) + 1, 0,                                                      \
                 if (b == 0) DD_ADVANCE(xc)                                                              \
-                if (b >= 1 && b - 1 < Tl::X_CHUNKS) x_ptr[b - 1] = DD_X_AT(b - 1);)                     \
+                if (b >= 1 && b - 1 < Tl::X_CHUNKS) x_ptr[b - 1] = DD_X_AT(b - 1);                      \
+                e3_)                                                                                    \
         __syncthreads();                                                                                \
     }
+#define DD_SLICE(g_, wf_cur_, wf_next_, xg_) DD_SLICE_X(g_, wf_cur_, wf_next_, xg_, , , , )
     static_assert(Tl::X_CHUNKS + 1 <= Tl::FB && Tl::FB >= 2, "one extra piece of work per MFMA");
+
+    // The result on its way out.  Accumulator i of lane l is output column 8*(i/4) + 4*(l/32) + i%4 of token l%32
+    // inside its 32x32 tile: four consecutive columns per group, one 8-byte LDS store.
+    // In the copy-out thread `tid` moves the 16-byte piece tid % 32 of rows tid / 32 + 16 i, i = 0..9; rows past
+    // the last token repeat the last valid row (same bytes to the same place), so no piece needs a predicate.
+    bf16x4 parked[Tl::FA][Tl::FB][4];
+    uint16_t *parked_dst = C;  // row 0 of the parked tile, this thread's piece
+    int parked_rows = 1;       // valid token rows of the parked tile
+    const int out_row0 = tid / (BN / 8), out_piece = tid % (BN / 8);
+#define DD_PARK /* the tile is complete */                                                              \
+    {                                                                                                   \
+        _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a)                                              \
+            _Pragma("unroll") for (int b = 0; b < Tl::FB; ++b)                                          \
+                _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                         \
+                    f32x4 v = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]}; \
+                    parked[a][b][q] = __builtin_convertvector(v, bf16x4);                               \
+                    _Pragma("unroll") for (int i = 0; i < 4; ++i) acc[a][b][4 * q + i] = 0.f;           \
+                }                                                                                       \
+        {                                                                                               \
+            int matrix = (out_tn * BN) / c_cols;                                                        \
+            int col = out_tn * BN - matrix * c_cols + out_piece * 8;                                    \
+            _Pragma("unroll") for (int hop = 0; hop < 2; ++hop)                                         \
+                if (col >= c_cols) {                                                                    \
+                    col -= c_cols;                                                                      \
+                    ++matrix;                                                                           \
+                }                                                                                       \
+            parked_dst = C + (size_t(matrix) * T + size_t(out_tm) * BM) * c_cols + col;                 \
+            parked_rows = min(BM, T - out_tm * BM);                                                     \
+        }                                                                                               \
+        const bool carry = out_tn + hop_n >= tiles_n;                                                   \
+        out_tn += hop_n - (carry ? tiles_n : 0);                                                        \
+        out_tm += hop_m + (carry ? 1 : 0);                                                              \
+    }
+    // token tile b_ of the parked result -> LDS
+#define DD_C_WRITE(b_)                                                                                  \
+    _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a)                                                  \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q)                                                   \
+            *reinterpret_cast<bf16x4 *>(c_buf + ((b_) * 32 + l32) * Tl::C_STRIDE +                      \
+                                        (wave * Tl::WN + a * 32 + 8 * q + 4 * half) * 2) = parked[a][b_][q];
+    // piece i_ of this thread's share of the copy-out, LDS -> memory
+#define DD_C_OUT(i_)                                                                                    \
+    {                                                                                                   \
+        const int r = min(out_row0 + (kMmThreads / (BN / 8)) * (i_), parked_rows - 1);                  \
+        *reinterpret_cast<u32x4 *>(parked_dst + size_t(unsigned(r)) * unsigned(c_cols)) =               \
+            *reinterpret_cast<const u32x4 *>(c_buf + r * Tl::C_STRIDE + out_piece * 16);                \
+    }
+    constexpr int kOutPieces = (BM * BN / 8 + kMmThreads - 1) / kMmThreads;
+    static_assert(Tl::FB == 5 && kOutPieces == 10, "the copy-out is dealt over the free places of two slices of five MFMAs per k-step");
 
     DD_LOAD_X(xg0)
     DD_LOAD_X(xg1)
@@ -603,37 +667,35 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
     for (int n = 0; n < Tl::X_CHUNKS; ++n) x_ptr[n] = DD_X_AT(n);  // slice 4
     __syncthreads();
     DD_LOAD_XF(xf0, 0, 0)
-    int kt = 0;
-    for (int g = 0; g < total; g += 2) {
+    int g = 0;
+    for (int kt = 0; kt < KT; kt += 2, g += 2) {  // the first tile
         DD_SLICE(g, wf0, wf1, xg0)
         DD_SLICE(g + 1, wf1, wf0, xg1)
-        kt += 2;
-        if (kt == KT) {  // uniform: the tile is complete
-            const int tm = out_tm, tn = out_tn;
-            // Accumulator i of lane l is output column 8*(i/4) + 4*(l/32) + i%4 of token l%32 inside its 32x32
-            // tile.  (The copy-out of the previous tile finished before the barriers of this tile's slices.)
-#pragma unroll
-            for (int a = 0; a < Tl::FA; ++a)
-#pragma unroll
-                for (int b = 0; b < Tl::FB; ++b)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        f32x4 v = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
-                        const bf16x4 h = __builtin_convertvector(v, bf16x4);
-                        const int t_local = b * 32 + l32;
-                        const int j_local = wave * Tl::WN + a * 32 + 8 * q + 4 * half;
-                        *reinterpret_cast<bf16x4 *>(c_buf + t_local * Tl::C_STRIDE + j_local * 2) = h;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) acc[a][b][4 * q + i] = 0.f;
-                    }
-            __syncthreads();
-            store_tile<BM, BN, kMmThreads>(C, c_buf, Tl::C_STRIDE, tm, tn, T, c_cols, tid);
-            kt = 0;
-            const bool carry = out_tn + hop_n >= tiles_n;
-            out_tn += hop_n - (carry ? tiles_n : 0);
-            out_tm += hop_m + (carry ? 1 : 0);
-        }
     }
+    DD_PARK
+    for (int tile = 1; tile < n_mine; ++tile) {
+        // first slice: the parked result goes to LDS (token tiles 0-2, then 3-4); second slice, after the barrier
+        // between the two: ten pieces per thread leave for memory
+        DD_SLICE_X(g, wf0, wf1, xg0, if (b >= 2) { DD_C_WRITE(b - 2) }, if (b == 2 || b == 3) { DD_C_WRITE(b + 1) }, , )
+        DD_SLICE_X(g + 1, wf1, wf0, xg1, if (b >= 2) { DD_C_OUT(b - 2) }, if (b >= 2) { DD_C_OUT(b + 1) },
+                   if (b >= 3) { DD_C_OUT(b + 3) }, if (b == 4) { DD_C_OUT(8) DD_C_OUT(9) })
+        g += 2;
+        for (int kt = 2; kt < KT; kt += 2, g += 2) {
+            DD_SLICE(g, wf0, wf1, xg0)
+            DD_SLICE(g + 1, wf1, wf0, xg1)
+        }
+        DD_PARK
+    }
+    // the last tile: nothing left to hide its copy-out behind
+#pragma unroll
+    for (int b = 0; b < Tl::FB; ++b) { DD_C_WRITE(b) }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kOutPieces; ++i) { DD_C_OUT(i) }
+#undef DD_PARK
+#undef DD_C_WRITE
+#undef DD_C_OUT
+#undef DD_SLICE_X
 #undef DD_STEP
 #undef DD_XF_ONE
 #undef DD_ADVANCE
