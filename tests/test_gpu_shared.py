@@ -132,3 +132,32 @@ def test_group_rules():
     # no tokens: nothing is launched, empty results come back
     assert dd.dd_fwd_shared(torch.zeros((0, 128), dtype=torch.bfloat16, device="cuda"), prepared).shape == (3, 0, 256)
     assert dd.dd_bwd_input_shared(torch.zeros((3, 0, 256), dtype=torch.bfloat16, device="cuda"), prepared).shape == (0, 128)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_groups(seed):
+    """Seeded random shapes (feature counts multiples of 128 up to 1024, any K, any token count up to 2000, one to
+    four sets): the group calls, the plain prepared calls and the self-contained calls against the oracle."""
+    rng = np.random.default_rng(9000 + seed)
+    M, N = (int(rng.integers(1, 9)) * 128 for _ in range(2))
+    D = max(M, N)
+    K = int(rng.integers(1, D + 1)) if seed % 3 == 0 else int(rng.integers(1, D // 8 + 2))
+    T = int(rng.integers(1, 2001))
+    S = int(rng.integers(1, 5))
+    offsets, values, X, dY = group_case(M, N, K, T, S, seed=seed)
+    d_off, d_val = torch.from_numpy(offsets).cuda(), to_dev(values, "bf16")
+    d_X, d_dY = to_dev(X, "bf16"), to_dev(dY, "bf16")
+    prepared = dd.dd_prepare_shared(d_off, d_val, M, N)
+    Y = dd.dd_fwd_shared(d_X, prepared)
+    dX = dd.dd_bwd_input_shared(d_dY, prepared)
+    ref_Y, ref_dX = oracle_group(offsets, values, X, dY, M, N)
+    for s in range(S):
+        assert rel_err(to_host(Y[s]), ref_Y[s]) <= TOL["bf16"], (M, N, K, T, S, s)
+    assert rel_err(to_host(dX), ref_dX) <= TOL["bf16"], (M, N, K, T, S)
+    s = int(rng.integers(0, S))
+    Y1 = dd.dd_fwd(d_X, d_off[s], d_val[s], N)                       # kernel family by shape and density
+    dX1 = dd.dd_bwd_input(d_dY[s], d_off[s], d_val[s], M)
+    dV1 = dd.dd_bwd_weight(d_X, d_dY[s], d_off[s])
+    assert rel_err(to_host(Y1), ref_Y[s]) <= TOL["bf16"], (M, N, K, T, S, s)
+    assert rel_err(to_host(dX1), orc.bwd_input(np.ascontiguousarray(dY[s]), offsets[s], values[s], M)) <= TOL["bf16"]
+    assert rel_err(to_host(dV1), orc.bwd_weight(X, np.ascontiguousarray(dY[s]), offsets[s])) <= TOL_DV
