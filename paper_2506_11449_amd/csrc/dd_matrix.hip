@@ -218,9 +218,11 @@ __device__ __forceinline__ void store_tile_piece(uint16_t *__restrict__ C, const
             col -= c_cols;
             ++matrix;
         }
+    // The result is not read again by this kernel: a streaming store keeps it from piling up dirty in the L2, which
+    // would otherwise be written back in one piece when the kernel ends (measured: 2 us of a 22 us product).
     if (row < BM && t < T)
-        *reinterpret_cast<u32x4 *>(C + (size_t(matrix) * T + t) * c_cols + col) =
-            *reinterpret_cast<const u32x4 *>(tile + row * tile_stride + ch * 16);
+        __builtin_nontemporal_store(*reinterpret_cast<const u32x4 *>(tile + row * tile_stride + ch * 16),
+                                    reinterpret_cast<u32x4 *>(C + (size_t(matrix) * T + t) * c_cols + col));
 }
 
 template <int BM, int BN, int THREADS>
@@ -648,8 +650,8 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
 #define DD_C_OUT(i_)                                                                                    \
     {                                                                                                   \
         const int r = min(out_row0 + (kMmThreads / (BN / 8)) * (i_), parked_rows - 1);                  \
-        *reinterpret_cast<u32x4 *>(parked_dst + size_t(unsigned(r)) * unsigned(c_cols)) =               \
-            *reinterpret_cast<const u32x4 *>(c_buf + r * Tl::C_STRIDE + out_piece * 16);                \
+        __builtin_nontemporal_store(*reinterpret_cast<const u32x4 *>(c_buf + r * Tl::C_STRIDE + out_piece * 16), \
+                                    reinterpret_cast<u32x4 *>(parked_dst + size_t(unsigned(r)) * unsigned(c_cols))); \
     }
     constexpr int kOutPieces = (BM * BN / 8 + kMmThreads - 1) / kMmThreads;
     static_assert(Tl::FB == 5 && kOutPieces == 10, "the copy-out is dealt over the free places of two slices of five MFMAs per k-step");
