@@ -83,7 +83,7 @@ __device__ __forceinline__ bf16x8 read_transposed(const unsigned char *p0, const
 // partial[split][k][p] for the representatives k of this tile's active offsets
 template <int TP, int TQ>
 __global__ __launch_bounds__(kWgT, kWgPerCu) void wgrad_mm_kernel(int T, int D, int L, int K, int tiles_p,
-                                                                  int tiles_q, int splits, int slices,
+                                                                  int tiles_q, int splits, int slices, int skew,
                                                                   const uint16_t *__restrict__ A,
                                                                   const uint16_t *__restrict__ B,
                                                                   const int *__restrict__ offsets,
@@ -105,8 +105,13 @@ __global__ __launch_bounds__(kWgT, kWgPerCu) void wgrad_mm_kernel(int T, int D, 
     if (split >= splits) return;
     const int tile = local % tiles;
     const int p0 = (tile / tiles_q) * TP, q0 = (tile % tiles_q) * TQ;
-    // chunk `split` owns the 32-token slices [split * slices / splits, (split + 1) * slices / splits)
-    const int slice_begin = int(int64_t(split) * slices / splits), slice_end = int(int64_t(split + 1) * slices / splits);
+    // Chunk `split` owns the 32-token slices [begin(split), begin(split + 1)), begin(s) = s * slices / splits
+    // + skew * (2 min(s, splits / 2) - s): the chunks of the first half of the workgroups are `skew` slices longer
+    // than an even share, those of the second half as much shorter (skew = 0: even shares).
+    const int half_splits = splits / 2;
+    const int slice_begin = int(int64_t(split) * slices / splits) + skew * (2 * min(split, half_splits) - split);
+    const int slice_end =
+        int(int64_t(split + 1) * slices / splits) + skew * (2 * min(split + 1, half_splits) - (split + 1));
     const int t_begin = slice_begin * kSliceTokens;
     const int t_end = min(slice_end * kSliceTokens, T);
     const int n_steps = (slice_end - slice_begin) * (kSliceTokens / kTS);  // even, at least 2
@@ -438,7 +443,8 @@ struct WgradPlan {
     int tp, tq;            // tile
     int tiles_p, tiles_q;
     int splits;            // token chunks (a multiple of the XCD count unless T is tiny)
-    int slices;            // T in units of 64 tokens
+    int slices;            // T in units of 32 tokens
+    int skew;              // slices moved from each chunk of the second half of the workgroups to one of the first
     int grid;
 };
 
@@ -463,6 +469,15 @@ static WgradPlan plan_wgrad(int64_t T, int D, int L)
     pl.splits = int(splits);
     const int rounds = (pl.splits + kWgXcds - 1) / kWgXcds;
     pl.grid = rounds * tiles * kWgXcds;
+    // When the grid is exactly the two workgroups per CU that fit, the second 256 get their first tokens about
+    // 1.5 us after the first 256 (the burst of first requests is served in order) and would finish their main
+    // loops as much later, alone on their CUs next to the first ones' epilogues.  Giving them two slices (four
+    // k-steps) less and the first ones two more lets both loops end together (measured on the ViT-Base attention
+    // layer: between 0.2 and 0.7 us of 22, box by box).  The split is a fixed function of the shape, so results stay reproducible.
+    // (Workgroup b works on chunk (b / 8 / tiles) * 8 + b % 8: with an even number of chunks per XCD the first 256
+    // workgroups are exactly the first half of the chunks.)
+    pl.skew = (pl.grid == 256 * kWgPerCu && per_xcd % 2 == 0 && splits == int64_t(per_xcd) * kWgXcds &&
+               slices / splits >= 8) ? 2 : 0;
     return pl;
 }
 
@@ -492,7 +507,7 @@ static hipError_t launch_wgrad_mm(const WeightGradArgs &a, const WgradPlan &pl, 
     }
     const int lds_bytes = Tl::LdsBytes;
     hipLaunchKernelGGL((wgrad_mm_kernel<TP, TQ>), dim3(pl.grid), dim3(kWgT), lds_bytes, stream, int(a.T), a.D, a.L,
-                       a.K, pl.tiles_p, pl.tiles_q, pl.splits, pl.slices,
+                       a.K, pl.tiles_p, pl.tiles_q, pl.splits, pl.slices, pl.skew,
                        static_cast<const uint16_t *>(a.A), static_cast<const uint16_t *>(a.B), a.offsets, partial);
     return hipGetLastError();
 }
