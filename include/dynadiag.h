@@ -22,7 +22,8 @@
  *     (size from dd_workspace_bytes, 256-byte aligned; may be NULL when that size is 0).
  *   - All matrices are row-major and contiguous.  Inputs and outputs must not overlap.
  *   - Outputs are overwritten.  Work is enqueued on `hip_stream` (a hipStream_t passed as
- *     void*, NULL = the default stream) and the call returns without waiting for it.
+ *     void*, NULL = the default stream) and the call returns without waiting for it.  The
+ *     stream's device must be the current device of the calling thread.
  *   - Errors are reported by the return value; nothing is thrown and nothing aborts.
  *     DD_ERR_INVALID_ARG: null pointer, tokens < 0, features < 1, K < 1, K > D, unknown
  *     dtype or algo.  DD_ERR_WORKSPACE: ws_bytes below dd_workspace_bytes or ws misaligned.

@@ -6,6 +6,21 @@
 
 namespace dd {
 
+// Raises a kernel's limit of dynamic LDS, once per device: the attribute belongs to the kernel as loaded on the
+// current device, so a flag per process would leave every device but the first at the default limit.
+// `done` is a bit set of device ordinals, one per kernel (a function-local static at the call site).
+inline hipError_t allow_dynamic_lds(const void *kernel, int bytes, uint64_t &done)
+{
+    int device = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = uint64_t(1) << (device & 63);
+    if (done & bit) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done |= bit;
+    return e;
+}
+
 // The two product shapes every forward / backward-input call reduces to
 // (D = long side, L = short side, offsets taken modulo D):
 //   gather:        dst[t, p] = sum_k src[t, (p + o_k) mod D] * v_k[p]              src [T x D], dst [T x L]

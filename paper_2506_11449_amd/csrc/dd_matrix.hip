@@ -726,13 +726,8 @@ static hipError_t launch_mm(int T, int NC, int KD, int a_cols, int c_cols, const
                             uint16_t *C, hipStream_t stream)
 {
     using Tl = MmTile<BM, BN, NW>;
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&mm_kernel<BM, BN, NW>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, Tl::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static uint64_t lds_allowed = 0;  // per device
+    if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&mm_kernel<BM, BN, NW>), Tl::LDS_BYTES, lds_allowed)) return e;
     const int tiles_m = (T + BM - 1) / BM, tiles_n = NC / BN;
     const int per_xcd = (tiles_m * tiles_n + kXcds - 1) / kXcds;
     hipLaunchKernelGGL((mm_kernel<BM, BN, NW>), dim3(per_xcd * kXcds), dim3(Tl::THREADS), Tl::LDS_BYTES, stream, T, NC, KD,
@@ -782,13 +777,8 @@ static hipError_t launch_mm_persistent(int T, int NC, int KD, int a_cols, int c_
     using Tl = MmTile<BM, BN, NW>;
     constexpr int kLds = kRing * Tl::X_BYTES + Tl::C_BYTES;
     static_assert(kLds <= 160 * 1024, "ring and result tile fit the LDS of a CU");
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&mm_persistent_kernel<BM, BN, NW>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static uint64_t lds_allowed = 0;  // per device
+    if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&mm_persistent_kernel<BM, BN, NW>), kLds, lds_allowed)) return e;
     const int tiles_m = (T + BM - 1) / BM, tiles_n = NC / BN;
     hipLaunchKernelGGL((mm_persistent_kernel<BM, BN, NW>), dim3(256), dim3(Tl::THREADS), kLds, stream, T, NC, KD,
                        a_cols, c_cols, tiles_m, tiles_n, A, Wf, C);

@@ -19,14 +19,8 @@ __global__ __launch_bounds__(kSelectThreads) void select_topk_kernel(
 hipError_t launch_select(int batch, int D, int K, const float *scores, int *out, hipStream_t stream)
 {
     if (D <= kSelectLdsKeys) {
-        static bool configured = false;
-        if (!configured) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&select_topk_kernel<true>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               kSelectLdsKeys * int(sizeof(uint32_t)));
-            if (e != hipSuccess) return e;
-            configured = true;
-        }
+        static uint64_t lds_allowed = 0;  // per device
+        if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&select_topk_kernel<true>), kSelectLdsKeys * int(sizeof(uint32_t)), lds_allowed)) return e;
         hipLaunchKernelGGL(select_topk_kernel<true>, dim3(batch), dim3(kSelectThreads), size_t(D) * sizeof(uint32_t),
                            stream, D, K, scores, out);
     } else {

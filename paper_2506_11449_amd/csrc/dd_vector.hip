@@ -167,23 +167,13 @@ static hipError_t launch_tiled(const ProductArgs &a, hipStream_t stream, size_t 
     const st *src = static_cast<const st *>(a.src), *values = static_cast<const st *>(a.values);
     st *dst = static_cast<st *>(a.dst);
     if (a.masked) {
-        static bool configured = false;
-        if (!configured) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&product_tiled_kernel<S, TT, true>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-            if (e != hipSuccess) return e;
-            configured = true;
-        }
+        static uint64_t lds_allowed = 0;  // per device
+        if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&product_tiled_kernel<S, TT, true>), 160 * 1024, lds_allowed)) return e;
         hipLaunchKernelGGL((product_tiled_kernel<S, TT, true>), dim3(grid), dim3(kProdThreads), lds, stream, a.T, a.D,
                            a.L, a.K, src, a.offsets, values, dst);
     } else {
-        static bool configured = false;
-        if (!configured) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&product_tiled_kernel<S, TT, false>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-            if (e != hipSuccess) return e;
-            configured = true;
-        }
+        static uint64_t lds_allowed = 0;  // per device
+        if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&product_tiled_kernel<S, TT, false>), 160 * 1024, lds_allowed)) return e;
         hipLaunchKernelGGL((product_tiled_kernel<S, TT, false>), dim3(grid), dim3(kProdThreads), lds, stream, a.T, a.D,
                            a.L, a.K, src, a.offsets, values, dst);
     }
