@@ -111,6 +111,17 @@ def test_prepare_rules(lib):
     assert lib.dd_bwd_input(ctypes.byref(ok), one, None, None, one, ctypes.c_void_p(512), need - 1, None) == 3
 
 
+def test_feature_count_limit(lib):
+    one = ctypes.c_void_p(256)
+    widest = _layer(T=2, M=65535, N=8, K=3)
+    too_wide = _layer(T=2, M=65536, N=8, K=3)
+    assert lib.dd_workspace_bytes(binding.DD_OP_FWD, ctypes.byref(too_wide), 0) == 0
+    for fn in (lib.dd_fwd, lib.dd_bwd_input):
+        assert fn(ctypes.byref(too_wide), one, one, one, one, None, 0, None) == 2
+        assert fn(ctypes.byref(widest), None, one, one, one, None, 0, None) == 1   # accepted up to the null pointer
+    assert lib.dd_bwd_weight(ctypes.byref(too_wide), one, one, one, one, None, 0, None) == 2
+
+
 def test_select_prepare_rules(lib):
     one = ctypes.c_void_p(256)
     blk = ctypes.c_void_p(512)

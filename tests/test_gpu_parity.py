@@ -308,6 +308,14 @@ def test_vitb_attention_projection_full_as_benchmarked():
     assert rel_err(to_host(dV), orc.bwd_weight(X, dY, offsets)) <= TOL_DV
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("M,N", [(65535, 8), (8, 65535)])
+def test_widest_layer(M, N, dtype):
+    """The largest feature count the products take (65535 candidate diagonals), in both orientations."""
+    offsets, values, X, dY = random_case(M, N, 3, 3, dtype, seed=M + 2 * N, offsets=[65534, 0, -40000])
+    check_against_oracle(offsets, values, X, dY, dtype, ALGOS["auto"])
+
+
 @pytest.mark.parametrize("algo", ["vector", "matrix"])
 def test_many_tokens_sampled(algo):
     """300001 tokens through a narrow layer: thousands of tiles per product, token counts far past any 16-bit grid
