@@ -237,6 +237,8 @@ def main():
     roofline.update({"executed_on": "matrix cores (dense contraction over all D candidate diagonals)"
                      if args.algo != "vector" and layer.dtype == "bf16" else "vector ALUs",
                      "dense_equivalent_tflops": 2.0 * T * M * N / dom_s / 1e12,
+                     # the dense contraction the matrix cores execute, against their published bf16 peak
+                     "dense_equivalent_frac_of_mfma_peak": 2.0 * T * M * N / dom_s / 1e12 / 2500.0,
                      "kernel": dominant, "avg_launch_us": dom_s * 1e6, "flops_per_launch": flops_product,
                      "bytes_per_launch": dom_bytes, "flop_per_byte": intensity,
                      "achieved_tflops": flops_product / dom_s / 1e12, "achieved_gbs": dom_bytes / dom_s / 1e9,
