@@ -31,7 +31,9 @@
  *     products: max(M, N) > 65535, or DD_ALGO_MATRIX / DD_ALGO_PREPARED forced where the matrix-core
  *     kernels do not apply.  They cover bf16 storage, 16-byte aligned matrices and M, N both multiples
  *     of 128 (dd_bwd_weight: both multiples of 192, or both of 128), max(M, N) <= 8192; DD_ALGO_AUTO
- *     takes them there when K / max(M, N) >= 1/48 and the vector kernels everywhere else.
+ *     takes them there when K / max(M, N) >= 1/48 and the vector kernels everywhere else -- also for a matrix
+ *     that is not 16-byte aligned (a view that starts at an odd element): such a call is legal under DD_ALGO_AUTO
+ *     and several times slower; DD_ALGO_MATRIX / DD_ALGO_PREPARED report it as DD_ERR_UNSUPPORTED instead.
  *     DD_ERR_HIP: the launch itself failed.
  *   - tokens == 0 is legal: fwd / bwd_input return DD_OK without a launch; bwd_weight
  *     writes zeros.
@@ -110,8 +112,8 @@ dd_status dd_fwd(const dd_layer *layer, const void *X, const int32_t *offsets, c
  *   prepared: dd_workspace_bytes(DD_OP_PREPARE, layer, 0) bytes, 256-byte aligned, owned by the caller and
  *   left alone by every other call; valid until offsets or values change.
  * Afterwards dd_fwd / dd_bwd_input take layer->algo = DD_ALGO_PREPARED with ws = prepared (their offsets
- * and values arguments are then not read).  dd_bwd_weight treats DD_ALGO_PREPARED like DD_ALGO_MATRIX and
- * needs its own scratch.  layer->tokens is not used here.
+ * and values arguments are then not read).  dd_bwd_weight treats DD_ALGO_PREPARED exactly like DD_ALGO_MATRIX
+ * (DD_ERR_UNSUPPORTED where the matrix-core kernels do not apply) and needs its own scratch.  layer->tokens is not used here.
  * DD_ERR_UNSUPPORTED where DD_ALGO_MATRIX would be (dtype other than bf16, feature counts that are not
  * multiples of 128).
  */

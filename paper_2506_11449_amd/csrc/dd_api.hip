@@ -66,6 +66,18 @@ bool wants_matrix_wgrad(const dd_layer *l, const Shape &s)
     return l->algo == DD_ALGO_MATRIX || l->algo == DD_ALGO_PREPARED || int64_t(l->K) * 48 >= s.D;
 }
 
+// Scratch of dd_bwd_weight.  A forced matrix-core call runs those kernels or fails, so it needs their partial
+// sums only.  Under DD_ALGO_AUTO the family is settled at the call, once the alignment of X and dY is known, and
+// the two families cut the tokens into different numbers of chunks: the size covers whichever of them runs.
+size_t weight_grad_ws_bytes(const dd_layer *l, const Shape &s)
+{
+    const size_t vector = dd::weight_grad_vector_ws_bytes(l->tokens, s.D, s.L, l->K, l->dtype == DD_BF16);
+    if (!wants_matrix_wgrad(l, s)) return vector;
+    const size_t matrix = dd::weight_grad_matrix_ws_bytes(l->tokens, s.D, s.L, l->K);
+    if (l->algo == DD_ALGO_MATRIX || l->algo == DD_ALGO_PREPARED) return matrix;
+    return matrix > vector ? matrix : vector;
+}
+
 constexpr int kMaxSets = 8;
 
 // `sets` > 1: a group of equally shaped layers sharing their input, operands prepared by dd_prepare_shared
@@ -133,9 +145,7 @@ size_t dd_workspace_bytes(int op, const dd_layer *layer, int32_t batch)
     case DD_OP_PREPARE:
         return dd::product_matrix_supported(1, s.D, s.L, layer->dtype == DD_BF16) ? prepared_bytes(s) : 0;
     case DD_OP_BWD_WEIGHT:
-        return wants_matrix_wgrad(layer, s) ? dd::weight_grad_matrix_ws_bytes(layer->tokens, s.D, s.L, layer->K)
-                                            : dd::weight_grad_vector_ws_bytes(layer->tokens, s.D, s.L, layer->K,
-                                                                               layer->dtype == DD_BF16);
+        return weight_grad_ws_bytes(layer, s);
     default:
         return 0;
     }
@@ -246,8 +256,13 @@ dd_status dd_bwd_weight(const dd_layer *layer, const void *X, const void *dY, co
     if (layer->tokens > 0 && (!X || !dY)) return DD_ERR_INVALID_ARG;
     if (dd_status st = check_ws(ws, ws_bytes, dd_workspace_bytes(DD_OP_BWD_WEIGHT, layer, 0))) return st;
     bool matrix = wants_matrix_wgrad(layer, s);
-    if (matrix && !(aligned16(X) && aligned16(dY))) matrix = false;
-    if (layer->algo == DD_ALGO_MATRIX && !matrix) return DD_ERR_UNSUPPORTED;
+    if (matrix && !(aligned16(X) && aligned16(dY))) matrix = false;  // 16-byte transfers into LDS
+    if ((layer->algo == DD_ALGO_MATRIX || layer->algo == DD_ALGO_PREPARED) && !matrix) return DD_ERR_UNSUPPORTED;
+    // the family that runs must fit the scratch that was checked (the two cut the tokens differently)
+    const size_t runs_in = matrix ? dd::weight_grad_matrix_ws_bytes(layer->tokens, s.D, s.L, layer->K)
+                                  : dd::weight_grad_vector_ws_bytes(layer->tokens, s.D, s.L, layer->K,
+                                                                    layer->dtype == DD_BF16);
+    if (ws_bytes < runs_in) return DD_ERR_WORKSPACE;
     dd::WeightGradArgs a;
     a.T = layer->tokens;
     a.D = s.D;

@@ -4,20 +4,25 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace dd {
 
 // Raises a kernel's limit of dynamic LDS, once per device: the attribute belongs to the kernel as loaded on the
 // current device, so a flag per process would leave every device but the first at the default limit.
 // `done` is a bit set of device ordinals, one per kernel (a function-local static at the call site).
-inline hipError_t allow_dynamic_lds(const void *kernel, int bytes, uint64_t &done)
+// Host threads may launch at the same time: the bits are set atomically, and two threads that both find a bit
+// clear merely set the same attribute twice.  Devices past ordinal 63 are not remembered (the attribute is set
+// on every launch there).
+inline hipError_t allow_dynamic_lds(const void *kernel, int bytes, std::atomic<uint64_t> &done)
 {
     int device = 0;
     hipError_t e = hipGetDevice(&device);
     if (e != hipSuccess) return e;
-    const uint64_t bit = uint64_t(1) << (device & 63);
-    if (done & bit) return hipSuccess;
+    const uint64_t bit = device < 64 ? uint64_t(1) << device : 0;
+    if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
     e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    if (e == hipSuccess) done |= bit;
+    if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
     return e;
 }
 

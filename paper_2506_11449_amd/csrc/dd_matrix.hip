@@ -25,12 +25,6 @@
 #include "dd_launch.h"
 #include "dd_select_block.h"
 
-// Tuning hooks for experiments (normal builds leave them alone): waves per workgroup, and
-// -DDD_MM_FORCE=BM,BN,NW to pin one tile shape.
-#ifndef DD_MM_WAVES
-#define DD_MM_WAVES 8
-#endif
-
 namespace dd {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -461,7 +455,6 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
     const int wave = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
     const int KT = KD / kBK;  // even: feature counts are multiples of 128
-    const int total = n_mine * KT;  // k-slices of all my tiles, numbered through
 
     int x_row[Tl::X_CHUNKS], x_col[Tl::X_CHUNKS], x_dst[Tl::X_CHUNKS];
 #pragma unroll
@@ -726,7 +719,7 @@ static hipError_t launch_mm(int T, int NC, int KD, int a_cols, int c_cols, const
                             uint16_t *C, hipStream_t stream)
 {
     using Tl = MmTile<BM, BN, NW>;
-    static uint64_t lds_allowed = 0;  // per device
+    static std::atomic<uint64_t> lds_allowed{0};  // one bit per device
     if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&mm_kernel<BM, BN, NW>), Tl::LDS_BYTES, lds_allowed)) return e;
     const int tiles_m = (T + BM - 1) / BM, tiles_n = NC / BN;
     const int per_xcd = (tiles_m * tiles_n + kXcds - 1) / kXcds;
@@ -777,7 +770,7 @@ static hipError_t launch_mm_persistent(int T, int NC, int KD, int a_cols, int c_
     using Tl = MmTile<BM, BN, NW>;
     constexpr int kLds = kRing * Tl::X_BYTES + Tl::C_BYTES;
     static_assert(kLds <= 160 * 1024, "ring and result tile fit the LDS of a CU");
-    static uint64_t lds_allowed = 0;  // per device
+    static std::atomic<uint64_t> lds_allowed{0};  // one bit per device
     if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&mm_persistent_kernel<BM, BN, NW>), kLds, lds_allowed)) return e;
     const int tiles_m = (T + BM - 1) / BM, tiles_n = NC / BN;
     hipLaunchKernelGGL((mm_persistent_kernel<BM, BN, NW>), dim3(256), dim3(Tl::THREADS), kLds, stream, T, NC, KD,
@@ -785,7 +778,7 @@ static hipError_t launch_mm_persistent(int T, int NC, int KD, int a_cols, int c_
     return hipGetLastError();
 }
 
-constexpr int kMmWaves = DD_MM_WAVES;
+constexpr int kMmWaves = 8;  // two waves per SIMD: one wave's waits hide behind the other's MFMAs
 
 // Largest tile whose workgroup count fills the 256 CUs in the fewest, fullest rounds.
 static int pick_tile(int64_t T, int NC)
@@ -824,9 +817,6 @@ hipError_t launch_product_matrix(const ProductArgs &a, hipStream_t stream)
     const uint16_t *A = static_cast<const uint16_t *>(a.src);
     uint16_t *C = static_cast<uint16_t *>(a.dst);
     const int T = int(a.T);
-#ifdef DD_MM_FORCE
-    return launch_mm<DD_MM_FORCE>(T, NC, KD, a_cols, c_cols, A, Wf, C, stream);  // tuning builds only
-#endif
     const int64_t tiles160 = ((a.T + 159) / 160) * ((NC + 255) / 256);
     if (NC % 256 == 0) {
         // more tiles than CUs: one workgroup per CU walks its tiles with the pipeline kept running

@@ -497,7 +497,7 @@ template <int TP, int TQ>
 static hipError_t launch_wgrad_mm(const WeightGradArgs &a, const WgradPlan &pl, float *partial, hipStream_t stream)
 {
     using Tl = WgTile<TP, TQ>;
-    static uint64_t lds_allowed = 0;  // per device
+    static std::atomic<uint64_t> lds_allowed{0};  // one bit per device
     if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&wgrad_mm_kernel<TP, TQ>), Tl::LdsBytes, lds_allowed)) return e;
     const int lds_bytes = Tl::LdsBytes;
     hipLaunchKernelGGL((wgrad_mm_kernel<TP, TQ>), dim3(pl.grid), dim3(kWgT), lds_bytes, stream, int(a.T), a.D, a.L,

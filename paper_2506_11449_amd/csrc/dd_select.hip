@@ -19,7 +19,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_topk_kernel(
 hipError_t launch_select(int batch, int D, int K, const float *scores, int *out, hipStream_t stream)
 {
     if (D <= kSelectLdsKeys) {
-        static uint64_t lds_allowed = 0;  // per device
+        static std::atomic<uint64_t> lds_allowed{0};  // one bit per device
         if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&select_topk_kernel<true>), kSelectLdsKeys * int(sizeof(uint32_t)), lds_allowed)) return e;
         hipLaunchKernelGGL(select_topk_kernel<true>, dim3(batch), dim3(kSelectThreads), size_t(D) * sizeof(uint32_t),
                            stream, D, K, scores, out);

@@ -167,12 +167,12 @@ static hipError_t launch_tiled(const ProductArgs &a, hipStream_t stream, size_t 
     const st *src = static_cast<const st *>(a.src), *values = static_cast<const st *>(a.values);
     st *dst = static_cast<st *>(a.dst);
     if (a.masked) {
-        static uint64_t lds_allowed = 0;  // per device
+        static std::atomic<uint64_t> lds_allowed{0};  // one bit per device
         if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&product_tiled_kernel<S, TT, true>), 160 * 1024, lds_allowed)) return e;
         hipLaunchKernelGGL((product_tiled_kernel<S, TT, true>), dim3(grid), dim3(kProdThreads), lds, stream, a.T, a.D,
                            a.L, a.K, src, a.offsets, values, dst);
     } else {
-        static uint64_t lds_allowed = 0;  // per device
+        static std::atomic<uint64_t> lds_allowed{0};  // one bit per device
         if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&product_tiled_kernel<S, TT, false>), 160 * 1024, lds_allowed)) return e;
         hipLaunchKernelGGL((product_tiled_kernel<S, TT, false>), dim3(grid), dim3(kProdThreads), lds, stream, a.T, a.D,
                            a.L, a.K, src, a.offsets, values, dst);

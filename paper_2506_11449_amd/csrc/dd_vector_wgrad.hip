@@ -224,7 +224,7 @@ int weight_grad_dot2_chunks(int64_t T, int D, int L, int K) { return plan_vw(T, 
 template <int NT, int MAXB>
 static hipError_t launch_vw(const WeightGradArgs &a, const VwPlan &pl, hipStream_t stream)
 {
-    static uint64_t lds_allowed = 0;  // per device
+    static std::atomic<uint64_t> lds_allowed{0};  // one bit per device
     if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&wgrad_dot2_kernel<NT, MAXB>), 160 * 1024, lds_allowed)) return e;
     hipLaunchKernelGGL((wgrad_dot2_kernel<NT, MAXB>), dim3(pl.grid), dim3(kVwThreads), pl.lds, stream, int(a.T), a.D,
                        a.L, a.K, pl.p_blocks, pl.k_blocks, pl.chunks, static_cast<const uint16_t *>(a.A),

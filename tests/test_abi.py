@@ -192,3 +192,16 @@ def test_binding_refuses_cpu_tensors():
     v = torch.zeros(2, 8)
     with pytest.raises(ValueError):
         dd.dd_fwd(X, off, v, 8)
+
+
+def test_weight_gradient_workspace_covers_whichever_family_runs(lib):
+    """Under DD_ALGO_AUTO the kernel family of dd_bwd_weight is settled at the call (X or dY not 16-byte aligned:
+    vector kernels), and the families cut the tokens into different numbers of chunks; the size asked for must cover
+    both.  A forced matrix-core call needs the matrix-core size only."""
+    for T, M, N, K in ((25216, 768, 3072, 307), (50432, 768, 768, 77), (25216, 1024, 4096, 410), (300, 768, 768, 77)):
+        sizes = {}
+        for algo in (binding.DD_ALGO_AUTO, binding.DD_ALGO_VECTOR, binding.DD_ALGO_MATRIX, binding.DD_ALGO_PREPARED):
+            l = _layer(T=T, M=M, N=N, K=K, dtype=1, algo=algo)
+            sizes[algo] = lib.dd_workspace_bytes(binding.DD_OP_BWD_WEIGHT, ctypes.byref(l), 0)
+        assert sizes[binding.DD_ALGO_AUTO] == max(sizes[binding.DD_ALGO_VECTOR], sizes[binding.DD_ALGO_MATRIX])
+        assert sizes[binding.DD_ALGO_PREPARED] == sizes[binding.DD_ALGO_MATRIX] > 0

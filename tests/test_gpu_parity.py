@@ -351,14 +351,15 @@ def test_vitb_mlp_sampled(which, algo):
 
 
 @pytest.mark.parametrize("algo", ["vector", "matrix", "auto"])
-@pytest.mark.parametrize("name", ["vitl_1024x1024_s80", "vitl_1024x1024_s95", "vitl_1024x4096_s90",
-                                  "vitl_4096x1024_s90"])
+@pytest.mark.parametrize("name", [l.name for l in synth.WORKLOADS["vitl"]])
 def test_vitl_sampled(name, algo):
+    """All nine layer x sparsity cases of the ViT-Large configuration (1024^2, 1024 -> 4096, 4096 -> 1024 at
+    80 / 90 / 95 %), 25216 tokens."""
     layer = next(l for l in synth.WORKLOADS["vitl"] if l.name == name)
     _sampled_check(layer, 4096, ALGOS[algo], n_rows=24, n_entries=128)
 
 
-@pytest.mark.parametrize("algo", ["auto"])
+@pytest.mark.parametrize("algo", ["matrix", "auto"])
 @pytest.mark.parametrize("which", [0, 4, 5])
 def test_vitb_stack_sampled(which, algo):
     """One block of the ViT-Base-depth stack at 256 x 197 tokens: attention projection, fc1, fc2."""
@@ -408,3 +409,46 @@ def test_select_feeds_forward_without_leaving_the_device():
     Y = dd.dd_fwd(to_dev(X, "f32"), d_off[0], to_dev(values, "f32"), layer.out_features)
     ref = orc.fwd(X, orc.select(scores, layer.K)[0], values, layer.out_features)
     assert rel_err(to_host(Y), ref) <= TOL["f32"]
+
+
+@pytest.mark.parametrize("M,N,K,T", [(768, 3072, 307, 25216), (768, 768, 77, 50432)])
+def test_weight_gradient_misaligned_inputs_stay_inside_the_workspace(M, N, K, T):
+    """X and dY that start one bf16 element past a 16-byte boundary: DD_ALGO_AUTO then runs the vector kernels, which
+    cut the tokens into more chunks than the matrix-core ones.  Called through the raw C ABI with exactly the scratch
+    dd_workspace_bytes asks for and a guard pattern behind it; sampled gradient entries against the oracle.  The
+    forced matrix-core family refuses such inputs."""
+    import ctypes
+    lib = dd.load_library()
+    layer = synth.Layer("misaligned", T, M, N, K, "bf16")
+    offsets, values, X, dY = synth.layer_inputs(layer, seed=31)
+    d_off = torch.from_numpy(offsets).cuda()
+
+    def shifted(a):  # a contiguous [rows x cols] bf16 view that starts 2 bytes past a 16-byte boundary
+        flat = torch.empty(a.size + 8, dtype=torch.bfloat16, device="cuda")
+        flat[1:1 + a.size] = to_dev(a, "bf16").reshape(-1)
+        v = flat[1:1 + a.size].view(a.shape)
+        assert v.data_ptr() % 16 == 2 and v.is_contiguous()
+        return v
+
+    d_X, d_dY = shifted(X), shifted(dY)
+    dV = torch.empty((K, min(M, N)), dtype=torch.float32, device="cuda")
+    l = dd.make_layer(T, M, N, K, torch.bfloat16, dd.DD_ALGO_AUTO)
+    need = dd.dd_workspace_bytes(dd.DD_OP_BWD_WEIGHT, l)
+    guard = 1 << 20
+    ws = torch.full((need + guard,), 0xCD, dtype=torch.uint8, device="cuda")
+    assert ws.data_ptr() % 256 == 0
+    vp = ctypes.c_void_p
+    stream = vp(torch.cuda.current_stream().cuda_stream)
+    st = lib.dd_bwd_weight(ctypes.byref(l), vp(d_X.data_ptr()), vp(d_dY.data_ptr()), vp(d_off.data_ptr()),
+                           vp(dV.data_ptr()), vp(ws.data_ptr()), need, stream)
+    assert st == 0
+    torch.cuda.synchronize()
+    assert bool((ws[need:] == 0xCD).all()), "dd_bwd_weight wrote past the scratch it asked for"
+    rng = np.random.default_rng(3)
+    ks, ps = rng.integers(0, K, 96), rng.integers(0, min(M, N), 96)
+    assert rel_err(to_host(dV)[ks, ps], orc.bwd_weight_sampled(X, dY, offsets, ks, ps)) <= TOL_DV
+    for algo in (dd.DD_ALGO_MATRIX, dd.DD_ALGO_PREPARED):
+        lm = dd.make_layer(T, M, N, K, torch.bfloat16, algo)
+        st = lib.dd_bwd_weight(ctypes.byref(lm), vp(d_X.data_ptr()), vp(d_dY.data_ptr()), vp(d_off.data_ptr()),
+                               vp(dV.data_ptr()), vp(ws.data_ptr()), need + guard, stream)
+        assert st == 2

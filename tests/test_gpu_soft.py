@@ -26,15 +26,18 @@ def test_soft_topk_forward_and_backward(B, D, K, temperature):
     g = synth.draw_normal((B, D), 1.0, seed=9, stream=D)
     got = to_host(dd.dd_soft_topk_bwd(d_scores_in, K, temperature, torch.from_numpy(g).cuda()))
     ref_b = orc.soft_topk_bwd(scores, K, temperature, g)
-    # an entry whose weight sits on the clamp within fp32 resolution may fall on either side of the min
+    # An entry whose weight sits on the clamp within fp32 resolution may fall on either side of the min, and then
+    # its own derivative is either the formula's or zero: those entries are left out of the comparison, every
+    # other entry is still checked (the clamp decision of entry i only enters entry i of the result).
     s = np.exp((scores.astype(np.float64) - scores.max(axis=1, keepdims=True)) / temperature)
     s /= s.sum(axis=1, keepdims=True)
-    if np.min(np.abs(K * s - 1.0)) > 1e-4:
-        # the derivative is (K / T) s_i (g_i - sum_j g_j s_j): when one weight takes nearly everything the
-        # bracket cancels to g_i (1 - s_i), so the fp32 rounding of s_i (2^-24) leaves an absolute error of
-        # about (K / T) |g| 2^-24 whatever the size of the result; a few of those are allowed on top
-        bound = 5 * TOL_SOFT * np.max(np.abs(ref_b)) + 4 * 2.0 ** -24 * (K / temperature) * np.max(np.abs(g))
-        assert np.max(np.abs(got - ref_b)) <= bound
+    decided = np.abs(K * s - 1.0) > 1e-4
+    assert decided.sum() >= decided.size - 2 * B  # the mask may drop a stray entry, never the test
+    # the derivative is (K / T) s_i (g_i - sum_j g_j s_j): when one weight takes nearly everything the
+    # bracket cancels to g_i (1 - s_i), so the fp32 rounding of s_i (2^-24) leaves an absolute error of
+    # about (K / T) |g| 2^-24 whatever the size of the result; a few of those are allowed on top
+    bound = 5 * TOL_SOFT * np.max(np.abs(ref_b)) + 4 * 2.0 ** -24 * (K / temperature) * np.max(np.abs(g))
+    assert np.max(np.abs(got - ref_b)[decided]) <= bound
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
