@@ -121,6 +121,19 @@ dd_status dd_prepare(const dd_layer *layer, const int32_t *offsets, const void *
                      size_t prepared_bytes, void *hip_stream);
 
 /*
+ * dd_prepare for n_layers independent layers of one shape (M -> N, K diagonals each) in one launch, as a training
+ * step over a stack of equal layers needs it after re-selecting every layer's diagonals (Sec. 3.2 Eq. 4 per layer).
+ *   offsets  [n_layers x K] int32, values [n_layers x K x L] dtype   in   (row i belongs to layer i; the offsets
+ *            are exactly what dd_select_diagonals writes for a batch of n_layers score vectors)
+ *   prepared n_layers * dd_workspace_bytes(DD_OP_PREPARE, layer, 0) bytes, 256-byte aligned: layer i's block is
+ *            the i-th piece of that size, bit for bit what dd_prepare builds for layer i, and is handed to
+ *            dd_fwd / dd_bwd_input (DD_ALGO_PREPARED) by itself.
+ * n_layers = 0 is legal (nothing is launched); more than 65535 layers: DD_ERR_UNSUPPORTED; other errors as dd_prepare.
+ */
+dd_status dd_prepare_batched(const dd_layer *layer, int32_t n_layers, const int32_t *offsets, const void *values,
+                             void *prepared, size_t prepared_bytes, void *hip_stream);
+
+/*
  * dd_select_diagonals for one score vector followed by dd_prepare on the diagonals it chose, as one call (one
  * launch for layers of up to 1024 candidate diagonals, where the launches are most of what the two steps cost;
  * two launches beyond).  The results are those of the two calls, bit for bit.

@@ -16,7 +16,7 @@ DD_ALGO_AUTO, DD_ALGO_VECTOR, DD_ALGO_MATRIX, DD_ALGO_PREPARED = 0, 1, 2, 3
 DD_OP_FWD, DD_OP_BWD_INPUT, DD_OP_BWD_WEIGHT, DD_OP_SELECT, DD_OP_SCALE_VALUES_BWD, DD_OP_PREPARE = 0, 1, 2, 3, 4, 5
 DD_OP_DIAGHEUR = 6
 
-EXPORTS = ("dd_workspace_bytes", "dd_fwd", "dd_prepare", "dd_select_prepare", "dd_prepare_shared", "dd_fwd_shared", "dd_bwd_input_shared",
+EXPORTS = ("dd_workspace_bytes", "dd_fwd", "dd_prepare", "dd_prepare_batched", "dd_select_prepare", "dd_prepare_shared", "dd_fwd_shared", "dd_bwd_input_shared",
            "dd_bwd_input", "dd_bwd_weight", "dd_select_diagonals",
            "dd_soft_topk", "dd_soft_topk_bwd", "dd_scale_values", "dd_scale_values_bwd", "dd_diag_magnitude",
            "dd_diagheur_update", "dd_status_string")
@@ -51,6 +51,8 @@ def load_library():
     lib.dd_fwd.argtypes = [lp, vp, vp, vp, vp, vp, sz, vp]
     lib.dd_prepare.argtypes = [lp, vp, vp, vp, sz, vp]
     lib.dd_select_prepare.argtypes = [lp, vp, vp, vp, vp, sz, vp]
+    lib.dd_prepare_batched.argtypes = [lp, i32, vp, vp, vp, sz, vp]
+    lib.dd_prepare_batched.restype = ctypes.c_int
     lib.dd_prepare_shared.argtypes = [lp, i32, vp, vp, vp, sz, vp]
     lib.dd_fwd_shared.argtypes = [lp, i32, vp, vp, sz, vp, vp]
     lib.dd_bwd_input_shared.argtypes = [lp, i32, vp, vp, sz, vp, vp]
@@ -163,6 +165,27 @@ def dd_prepare(offsets, values, in_features, out_features, prepared=None, stream
     if (prepared.in_features, prepared.out_features, prepared.K, prepared.dtype) != (M, N, K, values.dtype):
         raise ValueError("prepared block belongs to another layer")
     _check(load_library().dd_prepare(ref, _ptr(offsets), _ptr(values), _ptr(prepared.buf), prepared.buf.numel(), _stream(stream)))
+    return prepared
+
+
+def dd_prepare_batched(offsets, values, in_features, out_features, prepared=None, stream=None):
+    """dd_prepare for n independent layers of one shape in one launch: offsets int32 [n x K], values [n x K x min(M,N)].
+
+    Returns a list of n Prepared blocks (views into one buffer); pass it back as prepared= to refill it."""
+    M, N = int(in_features), int(out_features)
+    n, K = offsets.shape
+    _, ref, need = _plan(DD_OP_PREPARE, 0, M, N, K, values.dtype, DD_ALGO_PREPARED)
+    _dev(offsets, torch.int32, (n, K), "offsets")
+    _dev(values, values.dtype, (n, K, min(M, N)), "values")
+    if prepared is None:
+        buf = torch.empty(max(need * n, 1), dtype=torch.uint8, device=values.device)
+        prepared = [Prepared(buf[i * need:(i + 1) * need], M, N, K, values.dtype) for i in range(n)]
+        prepared[0].whole = buf
+    first = prepared[0]
+    if len(prepared) != n or (first.in_features, first.out_features, first.K, first.dtype) != (M, N, K, values.dtype):
+        raise ValueError("prepared blocks belong to other layers")
+    _check(load_library().dd_prepare_batched(ref, n, _ptr(offsets), _ptr(values), _ptr(first.whole), first.whole.numel(),
+                                             _stream(stream)))
     return prepared
 
 

@@ -175,6 +175,22 @@ dd_status dd_prepare(const dd_layer *layer, const int32_t *offsets, const void *
     return e == hipSuccess ? DD_OK : DD_ERR_HIP;
 }
 
+dd_status dd_prepare_batched(const dd_layer *layer, int32_t n_layers, const int32_t *offsets, const void *values,
+                             void *prepared, size_t prepared_bytes_given, void *hip_stream)
+{
+    Shape s;
+    if (dd_status st = check_layer(layer, &s)) return st;
+    if (n_layers < 0) return DD_ERR_INVALID_ARG;
+    if (n_layers == 0) return DD_OK;
+    if (!offsets || !values) return DD_ERR_INVALID_ARG;
+    if (n_layers > 65535 || layer->algo == DD_ALGO_VECTOR) return DD_ERR_UNSUPPORTED;
+    if (!dd::product_matrix_supported(1, s.D, s.L, layer->dtype == DD_BF16)) return DD_ERR_UNSUPPORTED;
+    if (dd_status st = check_ws(prepared, prepared_bytes_given, prepared_bytes(s) * size_t(n_layers))) return st;
+    const hipError_t e = dd::launch_prepare_matrix_batched(s.D, s.L, layer->K, n_layers, s.expanding, offsets, values,
+                                                           prepared, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? DD_OK : DD_ERR_HIP;
+}
+
 dd_status dd_select_prepare(const dd_layer *layer, const float *scores, const void *values, int32_t *offsets_out,
                             void *prepared, size_t prepared_bytes_given, void *hip_stream)
 {

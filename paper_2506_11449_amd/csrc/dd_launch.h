@@ -71,6 +71,11 @@ hipError_t launch_product_matrix(const ProductArgs &a, hipStream_t stream);
 hipError_t launch_prepare_matrix(int D, int L, int K, int sets, bool expanding, const int32_t *offsets,
                                  const void *values, void *forward_operand, void *backward_operand,
                                  hipStream_t stream);
+// The operands of `layers` independent layers of one shape in one launch (offsets [layers x K], values
+// [layers x K x L]): layer i's block, laid out as launch_prepare_matrix lays out a single layer (forward operand,
+// then backward-input operand), starts 2 * D * L elements after layer i-1's.
+hipError_t launch_prepare_matrix_batched(int D, int L, int K, int layers, bool expanding, const int32_t *offsets,
+                                         const void *values, void *prepared, hipStream_t stream);
 // Selection of the K diagonals from `scores` [D] and both dense operands from them in one launch (small layers
 // only: ask select_prepare_fused first).  offsets_out [K] receives the chosen offsets, ascending.
 bool select_prepare_fused(int D, int L, int K);

@@ -54,6 +54,7 @@ __device__ __forceinline__ size_t fragment_index(int j, int i, int KD)
 
 struct OperandPlace {
     int kd_total, col_step, k_step;
+    size_t block_step;  // elements from one set's operand to the next where every set has an operand of its own
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -66,7 +67,8 @@ struct OperandPlace {
 // blockIdx.y numbers the sets of a group of layers of one shape whose operands are stacked into one matrix
 // (set s uses offsets + s*K and values + s*K*L): an OperandPlace says where set s goes, s*col_step columns
 // to the right (the sets' outputs side by side) or s*k_step contraction indices down (their results summed),
-// inside a matrix of kd_total contraction indices.
+// inside a matrix of kd_total contraction indices; or, for layers that merely share a launch, set s has a whole
+// operand of its own block_step elements further on.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void materialize_kernel(int D, int L, int K, int masked_rows,
                                                           const int *__restrict__ offsets,
@@ -83,7 +85,7 @@ __global__ __launch_bounds__(256) void materialize_kernel(int D, int L, int K, i
     offsets += size_t(set) * K;
     values += size_t(set) * K * L;
     const OperandPlace place = long_major ? place_masked : place_gather;
-    uint16_t *Wf = long_major ? Wf_masked : Wf_gather;
+    uint16_t *Wf = (long_major ? Wf_masked : Wf_gather) + size_t(set) * place.block_step;
     for (int c = threadIdx.x; c < KD; c += 256) row[c] = 0.f;
     __syncthreads();
     for (int k = threadIdx.x; k < K; k += 256) {
@@ -734,13 +736,27 @@ hipError_t launch_prepare_matrix(int D, int L, int K, int sets, bool expanding, 
     // The forward product is the masked gather when the layer expands (M <= N), else the plain gather.  The sets'
     // forward operands stand side by side (every set has outputs of its own), their backward-input operands on top
     // of each other (the sets' contributions to the one input gradient add up in the contraction).
-    const OperandPlace side_by_side = {expanding ? L : D, expanding ? D : L, 0};
-    const OperandPlace stacked = {sets * (expanding ? D : L), 0, expanding ? D : L};
+    const OperandPlace side_by_side = {expanding ? L : D, expanding ? D : L, 0, 0};
+    const OperandPlace stacked = {sets * (expanding ? D : L), 0, expanding ? D : L, 0};
     hipLaunchKernelGGL(materialize_kernel, dim3(D + L, sets), dim3(256), size_t(D) * sizeof(float), stream, D, L, K, D,
                        offsets, static_cast<const uint16_t *>(values),
                        static_cast<uint16_t *>(expanding ? forward_operand : backward_operand),
                        static_cast<uint16_t *>(expanding ? backward_operand : forward_operand),
                        expanding ? side_by_side : stacked, expanding ? stacked : side_by_side);
+    return hipGetLastError();
+}
+
+hipError_t launch_prepare_matrix_batched(int D, int L, int K, int layers, bool expanding, const int32_t *offsets,
+                                         const void *values, void *prepared, hipStream_t stream)
+{
+    // layer i: forward operand at block i, backward-input operand D*L elements behind it, as launch_prepare_matrix
+    // lays out one layer
+    const size_t operand = size_t(D) * L;
+    const OperandPlace masked = {L, 0, 0, 2 * operand}, gather = {D, 0, 0, 2 * operand};
+    uint16_t *first = static_cast<uint16_t *>(prepared);
+    hipLaunchKernelGGL(materialize_kernel, dim3(D + L, layers), dim3(256), size_t(D) * sizeof(float), stream, D, L, K, D,
+                       offsets, static_cast<const uint16_t *>(values), expanding ? first : first + operand,
+                       expanding ? first + operand : first, masked, gather);
     return hipGetLastError();
 }
 
@@ -808,7 +824,7 @@ hipError_t launch_product_matrix(const ProductArgs &a, hipStream_t stream)
     uint16_t *Wf = static_cast<uint16_t *>(a.ws);
     if (!a.prepared) {
         if (a.src_sets != 1 || a.dst_sets != 1) return hipErrorInvalidValue;  // groups come prepared
-        const OperandPlace place = {KD, 0, 0};
+        const OperandPlace place = {KD, 0, 0, 0};
         hipLaunchKernelGGL(materialize_kernel, dim3(NC), dim3(256), size_t(KD) * sizeof(float), stream, a.D, a.L, a.K,
                            a.masked ? NC : 0, a.offsets, static_cast<const uint16_t *>(a.values), Wf, Wf, place, place);
         hipError_t e = hipGetLastError();
