@@ -190,6 +190,23 @@ dd_status dd_bwd_weight(const dd_layer *layer, const void *X, const void *dY, co
                         float *dValues, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * dd_bwd_weight for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without `ws`, same kernels,
+ * same results bit for bit; the partial sums of the token chunks go to an array inside the library,
+ * dd_static_scratch_bytes() bytes (32 MiB) per GPU, which every GPU the library runs on holds from the first such
+ * call until the process ends.  The call allocates and frees nothing.
+ *   DD_ERR_WORKSPACE  dd_workspace_bytes(DD_OP_BWD_WEIGHT, layer, 0) exceeds dd_static_scratch_bytes(); nothing is
+ *                     launched.  (Under DD_ALGO_AUTO that size covers both kernel families; where it is too large,
+ *                     DD_ALGO_MATRIX, which needs less, may still fit.)
+ * Every call on one GPU uses that GPU's one array: calls that overlap in time on one GPU (two streams, two
+ * threads) race and give wrong sums; calls in stream order, or on different GPUs, are safe.  Nothing has to be
+ * cleared between calls: the kernels write every partial sum before they read it.
+ */
+size_t dd_static_scratch_bytes(void);
+dd_status dd_bwd_weight_static(const dd_layer *layer, const void *X, const void *dY, const int32_t *offsets,
+                               float *dValues, void *hip_stream);
+
+/*
  * Hard TopK re-selection of the active diagonals (Sec. 3.2, Eq. 4): for each of `batch`
  * score vectors alpha [D], the indices of the K largest scores.
  *   Order between scores: larger first; equal scores (and -0 / +0) by lower index; NaN ranks

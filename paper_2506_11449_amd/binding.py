@@ -17,7 +17,7 @@ DD_OP_FWD, DD_OP_BWD_INPUT, DD_OP_BWD_WEIGHT, DD_OP_SELECT, DD_OP_SCALE_VALUES_B
 DD_OP_DIAGHEUR = 6
 
 EXPORTS = ("dd_workspace_bytes", "dd_fwd", "dd_prepare", "dd_prepare_batched", "dd_select_prepare", "dd_prepare_shared", "dd_fwd_shared", "dd_bwd_input_shared",
-           "dd_bwd_input", "dd_bwd_weight", "dd_select_diagonals",
+           "dd_bwd_input", "dd_bwd_weight", "dd_bwd_weight_static", "dd_static_scratch_bytes", "dd_select_diagonals",
            "dd_soft_topk", "dd_soft_topk_bwd", "dd_scale_values", "dd_scale_values_bwd", "dd_diag_magnitude",
            "dd_diagheur_update", "dd_status_string")
 
@@ -58,6 +58,10 @@ def load_library():
     lib.dd_bwd_input_shared.argtypes = [lp, i32, vp, vp, sz, vp, vp]
     lib.dd_bwd_input.argtypes = [lp, vp, vp, vp, vp, vp, sz, vp]
     lib.dd_bwd_weight.argtypes = [lp, vp, vp, vp, vp, vp, sz, vp]
+    lib.dd_bwd_weight_static.argtypes = [lp, vp, vp, vp, vp, vp]
+    lib.dd_bwd_weight_static.restype = ctypes.c_int
+    lib.dd_static_scratch_bytes.argtypes = []
+    lib.dd_static_scratch_bytes.restype = sz
     lib.dd_select_diagonals.argtypes = [i32, i32, i32, vp, vp, vp, sz, vp]
     f32 = ctypes.c_float
     lib.dd_soft_topk.argtypes = [i32, i32, i32, f32, vp, vp, vp]
@@ -66,7 +70,7 @@ def load_library():
     lib.dd_scale_values_bwd.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.dd_diag_magnitude.argtypes = [i32, i32, i32, vp, vp, vp]
     lib.dd_diagheur_update.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
-    for name in ("dd_diag_magnitude", "dd_diagheur_update", "dd_fwd", "dd_prepare", "dd_bwd_input", "dd_bwd_weight", "dd_select_diagonals", "dd_soft_topk",
+    for name in ("dd_diag_magnitude", "dd_diagheur_update", "dd_fwd", "dd_prepare", "dd_bwd_input", "dd_bwd_weight", "dd_bwd_weight_static", "dd_static_scratch_bytes", "dd_select_diagonals", "dd_soft_topk",
                  "dd_soft_topk_bwd", "dd_scale_values", "dd_scale_values_bwd"):
         getattr(lib, name).restype = ctypes.c_int
     lib.dd_status_string.argtypes = [ctypes.c_int]
@@ -319,6 +323,24 @@ def dd_bwd_weight(X, dY, offsets, dValues=None, algo=DD_ALGO_AUTO, ws=None, stre
     _dev(dValues, torch.float32, (K, min(M, N)), "dValues")
     wp, wn = _ws_for(need, X.device, ws)
     _check(_lib.dd_bwd_weight(ref, _ptr(X), _ptr(dY), _ptr(offsets), _ptr(dValues), wp, wn, _stream(stream)))
+    return dValues
+
+
+def dd_static_scratch_bytes():
+    return int(load_library().dd_static_scratch_bytes())
+
+
+def dd_bwd_weight_static(X, dY, offsets, dValues, algo=DD_ALGO_AUTO, stream=None):
+    """dd_bwd_weight without a workspace and without any allocation: dValues [K x min(M,N)] fp32 is the caller's."""
+    T, M = X.shape
+    N = dY.shape[1]
+    K = offsets.shape[0]
+    _, ref, _ = _plan(DD_OP_BWD_WEIGHT, T, M, N, K, X.dtype, algo)
+    _dev(X, X.dtype, (T, M), "X")
+    _dev(dY, X.dtype, (T, N), "dY")
+    _dev(offsets, torch.int32, (K,), "offsets")
+    _dev(dValues, torch.float32, (K, min(M, N)), "dValues")
+    _check(load_library().dd_bwd_weight_static(ref, _ptr(X), _ptr(dY), _ptr(offsets), _ptr(dValues), _stream(stream)))
     return dValues
 
 

@@ -5,6 +5,8 @@
 
 #include "dd_launch.h"
 
+#include <atomic>
+
 namespace {
 
 constexpr int kMaxFeatures = 65535;
@@ -384,6 +386,56 @@ dd_status dd_diagheur_update(int32_t D, int32_t K, int32_t n_drop, const int32_t
                                       static_cast<hipStream_t>(hip_stream)) == hipSuccess
                ? DD_OK
                : DD_ERR_HIP;
+}
+
+// ---------------------------------------------------------------------------------------------
+// dd_bwd_weight for callers that cannot allocate: the partial sums of the token chunks live in an array of
+// this library's own instead of a workspace of the caller's.
+// ---------------------------------------------------------------------------------------------
+}  // extern "C"
+
+namespace {
+
+constexpr size_t kStaticScratchBytes = size_t(32) << 20;
+// One copy per GPU, at an address of its own on each; host code must not use the name as an address.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> scratch_ptr[kMaxDevices];  // the array's address on each device, asked for once
+
+// The array's address on the current device (hipGetSymbolAddress answers for the device that is current).
+hipError_t static_scratch(void **ptr)
+{
+    int device = 0;
+    if (hipError_t e = hipGetDevice(&device)) return e;
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    void *p = scratch_ptr[device].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        scratch_ptr[device].store(p, std::memory_order_release);  // two threads racing here store the same address
+    }
+    *ptr = p;
+    return hipSuccess;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t dd_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+dd_status dd_bwd_weight_static(const dd_layer *layer, const void *X, const void *dY, const int32_t *offsets,
+                               float *dValues, void *hip_stream)
+{
+    Shape s;
+    if (dd_status st = check_layer(layer, &s)) return st;
+    // beyond the array: refused before anything is launched or looked up
+    if (weight_grad_ws_bytes(layer, s) > kStaticScratchBytes) return DD_ERR_WORKSPACE;
+    void *ptr = nullptr;
+    if (static_scratch(&ptr) != hipSuccess) return DD_ERR_HIP;
+    // The kernels overwrite every partial sum they later read, so what the last call left behind needs no clearing.
+    return dd_bwd_weight(layer, X, dY, offsets, dValues, ptr, kStaticScratchBytes, hip_stream);
 }
 
 const char *dd_status_string(dd_status status)
