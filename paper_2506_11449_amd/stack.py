@@ -55,7 +55,10 @@ def _to_dev_bf16(a, device):
 
 class StackStep:
     def __init__(self, blocks=12, tokens=256 * 197, sets_attn=4, sets_mlp=2, score_sets=4, seed=2506,
-                 distinct_sets=False, sparsity_percent=90, device="cuda:0"):
+                 distinct_sets=False, device_inputs=False, sparsity_percent=90, device="cuda:0"):
+        """distinct_sets: every buffer set of a shape holds values of its own (else set 0's values at other
+        addresses).  device_inputs: X and dY are drawn on the device (seeded torch generator) instead of on the host --
+        quicker for the benchmark; the parity tests draw on the host, where the oracle reads the same arrays."""
         self.blocks, self.tokens, self.seed, self.device = blocks, tokens, seed, torch.device(device)
         self.score_sets = score_sets
         K_attn = synth.num_diagonals(768, sparsity_percent)
@@ -80,13 +83,19 @@ class StackStep:
         self.host_inputs = {}
         for gi, g in enumerate(self.groups.values()):
             host = []
-            for s in range(g.sets if distinct_sets else 1):
+            if device_inputs:
+                gen = torch.Generator(device=self.device)
+                gen.manual_seed(seed + gi)
+                for s in range(g.sets if distinct_sets else 1):
+                    g.X.append(torch.randn((tokens, g.M), device=self.device, generator=gen).to(torch.bfloat16))
+                    g.dY.append(torch.randn((tokens, g.N), device=self.device, generator=gen).to(torch.bfloat16))
+            for s in range(0 if device_inputs else (g.sets if distinct_sets else 1)):
                 X = synth.round_to_bf16(synth.draw_normal((tokens, g.M), 1.0, seed, 1000 * gi + 10 * s + 1))
                 dY = synth.round_to_bf16(synth.draw_normal((tokens, g.N), 1.0, seed, 1000 * gi + 10 * s + 2))
                 host.append((X, dY))
                 g.X.append(_to_dev_bf16(X, self.device))
                 g.dY.append(_to_dev_bf16(dY, self.device))
-            for s in range(len(host), g.sets):  # same values at other addresses
+            for s in range(len(g.X), g.sets):  # same values at other addresses
                 g.X.append(g.X[0].clone())
                 g.dY.append(g.dY[0].clone())
             self.host_inputs[g.name] = host
