@@ -56,6 +56,9 @@ def parse():
     ap.add_argument("--no-configs", action="store_true", help="leave out the sub-lines of the smaller configurations")
     ap.add_argument("--offset-bands", type=int, default=0,
                     help="0: seeded uniform offsets (the benchmark); n > 0: the K diagonals in n runs of adjacent ones")
+    ap.add_argument("--per-layer", action="store_true",
+                    help="with --workload vitb_stack: time the distinct layers of one block one by one (select + prepare + "
+                         "three products each) instead of the whole stack step")
     ap.add_argument("--tune-dense", action="store_true",
                     help="search hipBLASLt / rocBLAS for the fastest solution of every dense GEMM the benchmark "
                          "compares with and write them to bench_dense_gemm_tuned.csv (minutes)")
@@ -219,6 +222,16 @@ class LayerBench:
         s = i % self.S
         self.dd.dd_bwd_input(self.dY[s], None, None, self.M, dX=self.dX[s], prepared=self.prepared)
 
+    def fwd_blocks(self, i):  # prepared operands, empty 32 x 16 operand blocks skipped
+        s = i % self.S
+        self.dd.dd_fwd(self.X[s], self.off[0], None, self.N, Y=self.Y[s], prepared=self.prepared,
+                       algo=self.dd.DD_ALGO_BLOCKS)
+
+    def bwd_input_blocks(self, i):
+        s = i % self.S
+        self.dd.dd_bwd_input(self.dY[s], self.off[0], None, self.M, dX=self.dX[s], prepared=self.prepared,
+                             algo=self.dd.DD_ALGO_BLOCKS)
+
     def bwd_weight(self, i):
         s = i % self.S
         self.dd.dd_bwd_weight(self.X[s], self.dY[s], self.off[0], dValues=self.dV, algo=self.algo, ws=self.ws)
@@ -251,6 +264,9 @@ class LayerBench:
             us["dd_fwd_self_contained"] = time_loop(torch, self.fwd_alone, n) * 1e3
             us["dd_bwd_input_self_contained"] = time_loop(torch, self.bwd_input_alone, n) * 1e3
             self.prepare(0)
+            if self.D <= 8192:
+                us["dd_fwd_blocks"] = time_loop(torch, self.fwd_blocks, n) * 1e3
+                us["dd_bwd_input_blocks"] = time_loop(torch, self.bwd_input_blocks, n) * 1e3
         line = {"layer": f"{self.M}->{self.N}", "tokens": self.T, "K": self.K, "dtype": self.layer.dtype,
                 "buffer_sets": self.S, "us": us,
                 "sparse_tflops": {k: self.flops() / us[k] / 1e6 for k in ("dd_fwd", "dd_bwd_input", "dd_bwd_weight")},
@@ -613,7 +629,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    if args.workload == "vitb_stack":
+    if args.workload == "vitb_stack" and not args.per_layer and args.offset_bands == 0:
         out = run_stack(args, torch, dd, synth, dense)
         if not args.no_configs:
             out["breakdown"]["configs"] = config_sublines(args, torch, dd, synth, dense)

@@ -64,7 +64,12 @@ typedef enum {
     DD_ALGO_AUTO = 0,
     DD_ALGO_VECTOR = 1, /* direct diagonal kernels on the vector ALUs: work ~ tokens*K*L   */
     DD_ALGO_MATRIX = 2, /* the diagonals rebuilt as a dense operand in scratch, product on the matrix cores */
-    DD_ALGO_PREPARED = 3 /* as DD_ALGO_MATRIX, with the dense operands already built by dd_prepare */
+    DD_ALGO_PREPARED = 3, /* as DD_ALGO_MATRIX, with the dense operands already built by dd_prepare */
+    DD_ALGO_BLOCKS = 4    /* as DD_ALGO_PREPARED, and the product skips every 32 x 16 block of the operand that no
+                             diagonal crosses; it also reads `offsets` (to tell which blocks those are).  For active
+                             sets that lie in runs of adjacent diagonals (Sec. 3.3: the learned masks cluster): with
+                             offsets spread uniformly nearly every block is crossed and DD_ALGO_PREPARED is faster.
+                             dd_fwd / dd_bwd_input only; max(M, N) <= 8192; dd_bwd_weight treats it as DD_ALGO_MATRIX. */
 } dd_algo;
 
 typedef enum {

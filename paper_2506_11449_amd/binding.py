@@ -12,7 +12,7 @@ import torch  # imported before the library so that both share one HIP runtime
 from .build import LIB_PATH
 
 DD_F32, DD_BF16 = 0, 1
-DD_ALGO_AUTO, DD_ALGO_VECTOR, DD_ALGO_MATRIX, DD_ALGO_PREPARED = 0, 1, 2, 3
+DD_ALGO_AUTO, DD_ALGO_VECTOR, DD_ALGO_MATRIX, DD_ALGO_PREPARED, DD_ALGO_BLOCKS = 0, 1, 2, 3, 4
 DD_OP_FWD, DD_OP_BWD_INPUT, DD_OP_BWD_WEIGHT, DD_OP_SELECT, DD_OP_SCALE_VALUES_BWD, DD_OP_PREPARE = 0, 1, 2, 3, 4, 5
 DD_OP_DIAGHEUR = 6
 
@@ -274,7 +274,9 @@ def _product(fn, op, src, offsets, values, n_src, n_dst, M, N, dst, algo, ws, st
     if prepared is not None:
         if (prepared.in_features, prepared.out_features, prepared.dtype) != (M, N, src.dtype):
             raise ValueError("prepared block belongs to another layer")
-        algo, K = DD_ALGO_PREPARED, prepared.K
+        algo, K = (DD_ALGO_BLOCKS if algo == DD_ALGO_BLOCKS else DD_ALGO_PREPARED), prepared.K
+        if algo == DD_ALGO_BLOCKS:
+            _dev(offsets, torch.int32, (K,), "offsets")
     else:
         K = offsets.shape[0]
         _dev(offsets, torch.int32, (K,), "offsets")
@@ -286,7 +288,8 @@ def _product(fn, op, src, offsets, values, n_src, n_dst, M, N, dst, algo, ws, st
     _dev(dst, src.dtype, (T, n_dst), names[1])
     if prepared is not None:
         wp, wn = _ptr(prepared.buf), prepared.buf.numel()
-        _check(fn(ref, _ptr(src), None, None, _ptr(dst), wp, wn, _stream(stream)))
+        _check(fn(ref, _ptr(src), _ptr(offsets) if algo == DD_ALGO_BLOCKS else None, None, _ptr(dst), wp, wn,
+                  _stream(stream)))
     else:
         wp, wn = _ws_for(need, src.device, ws)
         _check(fn(ref, _ptr(src), _ptr(offsets), _ptr(values), _ptr(dst), wp, wn, _stream(stream)))
@@ -296,7 +299,8 @@ def _product(fn, op, src, offsets, values, n_src, n_dst, M, N, dst, algo, ws, st
 def dd_fwd(X, offsets, values, out_features, Y=None, algo=DD_ALGO_AUTO, ws=None, stream=None, prepared=None):
     """Y = X . W_K.  X [T x M], offsets int32 [K], values [K x min(M,N)] -> Y [T x N].
 
-    With prepared= (from dd_prepare) offsets and values are not read and may be None."""
+    With prepared= (from dd_prepare) offsets and values are not read and may be None; with algo=DD_ALGO_BLOCKS
+    as well, the offsets are read (the product then skips the operand blocks no diagonal crosses)."""
     M, N = X.shape[1], int(out_features)
     return _product(load_library().dd_fwd, DD_OP_FWD, X, offsets, values, M, N, M, N, Y, algo, ws, stream, prepared,
                     ("X", "Y"))

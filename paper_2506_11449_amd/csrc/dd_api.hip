@@ -23,7 +23,7 @@ dd_status check_layer(const dd_layer *l, Shape *s)
     if (l->tokens < 0 || l->in_features < 1 || l->out_features < 1 || l->K < 1) return DD_ERR_INVALID_ARG;
     if (l->dtype != DD_F32 && l->dtype != DD_BF16) return DD_ERR_INVALID_ARG;
     if (l->algo != DD_ALGO_AUTO && l->algo != DD_ALGO_VECTOR && l->algo != DD_ALGO_MATRIX &&
-        l->algo != DD_ALGO_PREPARED)
+        l->algo != DD_ALGO_PREPARED && l->algo != DD_ALGO_BLOCKS)
         return DD_ERR_INVALID_ARG;
     const int D = l->in_features > l->out_features ? l->in_features : l->out_features;
     const int L = l->in_features < l->out_features ? l->in_features : l->out_features;
@@ -55,7 +55,8 @@ bool wants_matrix(const dd_layer *l, const Shape &s)
     if (l->algo == DD_ALGO_VECTOR) return false;
     // (a call without tokens launches nothing, whatever the family)
     if (!dd::product_matrix_supported(l->tokens > 0 ? l->tokens : 1, s.D, s.L, l->dtype == DD_BF16)) return false;
-    return l->algo == DD_ALGO_MATRIX || l->algo == DD_ALGO_PREPARED || int64_t(l->K) * 48 >= s.D;
+    return l->algo == DD_ALGO_MATRIX || l->algo == DD_ALGO_PREPARED || l->algo == DD_ALGO_BLOCKS ||
+           int64_t(l->K) * 48 >= s.D;
 }
 
 // the block dd_prepare fills: the operand of the forward product, then the one of the backward-input product
@@ -65,7 +66,8 @@ bool wants_matrix_wgrad(const dd_layer *l, const Shape &s)
 {
     if (l->algo == DD_ALGO_VECTOR) return false;
     if (!dd::weight_grad_matrix_supported(l->tokens, s.D, s.L, l->dtype == DD_BF16)) return false;
-    return l->algo == DD_ALGO_MATRIX || l->algo == DD_ALGO_PREPARED || int64_t(l->K) * 48 >= s.D;
+    return l->algo == DD_ALGO_MATRIX || l->algo == DD_ALGO_PREPARED || l->algo == DD_ALGO_BLOCKS ||
+           int64_t(l->K) * 48 >= s.D;
 }
 
 // Scratch of dd_bwd_weight.  A forced matrix-core call runs those kernels or fails, so it needs their partial
@@ -76,7 +78,7 @@ size_t weight_grad_ws_bytes(const dd_layer *l, const Shape &s)
     const size_t vector = dd::weight_grad_vector_ws_bytes(l->tokens, s.D, s.L, l->K, l->dtype == DD_BF16);
     if (!wants_matrix_wgrad(l, s)) return vector;
     const size_t matrix = dd::weight_grad_matrix_ws_bytes(l->tokens, s.D, s.L, l->K);
-    if (l->algo == DD_ALGO_MATRIX || l->algo == DD_ALGO_PREPARED) return matrix;
+    if (l->algo != DD_ALGO_AUTO) return matrix;
     return matrix > vector ? matrix : vector;
 }
 
@@ -86,8 +88,10 @@ constexpr int kMaxSets = 8;
 dd_status product(const dd_layer *l, const Shape &s, bool transposed, const void *src, const int32_t *offsets,
                   const void *values, void *dst, void *ws, size_t ws_bytes, void *stream, int sets = 1)
 {
-    const bool prepared = l->algo == DD_ALGO_PREPARED;
+    const bool blocks = l->algo == DD_ALGO_BLOCKS;  // prepared operands, and the offsets to tell which blocks are empty
+    const bool prepared = l->algo == DD_ALGO_PREPARED || blocks;
     if (!prepared && (!offsets || !values)) return DD_ERR_INVALID_ARG;
+    if (blocks && (!offsets || sets != 1)) return DD_ERR_INVALID_ARG;
     if (l->tokens > 0 && (!src || !dst)) return DD_ERR_INVALID_ARG;
     bool matrix = wants_matrix(l, s);
     if (prepared && !matrix) return DD_ERR_UNSUPPORTED;
@@ -96,6 +100,7 @@ dd_status product(const dd_layer *l, const Shape &s, bool transposed, const void
     if (l->tokens == 0) return DD_OK;
     if (matrix && !(aligned16(src) && aligned16(dst))) matrix = false;  // 16-byte vector accesses
     if ((l->algo == DD_ALGO_MATRIX || prepared) && !matrix) return DD_ERR_UNSUPPORTED;
+    if (blocks && !dd::product_blocks_supported(l->tokens, s.D, s.L, l->dtype == DD_BF16)) return DD_ERR_UNSUPPORTED;
     dd::ProductArgs a;
     a.T = l->tokens;
     a.D = s.D;
@@ -114,8 +119,9 @@ dd_status product(const dd_layer *l, const Shape &s, bool transposed, const void
         if (transposed) a.ws = static_cast<unsigned char *>(ws) + dd::product_matrix_ws_bytes(s.D, s.L) * size_t(sets);
         (transposed ? a.src_sets : a.dst_sets) = sets;
     }
-    const hipError_t e = matrix ? dd::launch_product_matrix(a, static_cast<hipStream_t>(stream))
-                                : dd::launch_product_vector(a, static_cast<hipStream_t>(stream));
+    const hipError_t e = blocks   ? dd::launch_product_blocks(a, static_cast<hipStream_t>(stream))
+                         : matrix ? dd::launch_product_matrix(a, static_cast<hipStream_t>(stream))
+                                  : dd::launch_product_vector(a, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? DD_OK : DD_ERR_HIP;
 }
 
@@ -142,7 +148,8 @@ size_t dd_workspace_bytes(int op, const dd_layer *layer, int32_t batch)
     switch (op) {
     case DD_OP_FWD:
     case DD_OP_BWD_INPUT:
-        if (layer->algo == DD_ALGO_PREPARED) return wants_matrix(layer, s) ? prepared_bytes(s) : 0;
+        if (layer->algo == DD_ALGO_PREPARED || layer->algo == DD_ALGO_BLOCKS)
+            return wants_matrix(layer, s) ? prepared_bytes(s) : 0;
         return wants_matrix(layer, s) ? dd::product_matrix_ws_bytes(s.D, s.L) : 0;
     case DD_OP_PREPARE:
         return dd::product_matrix_supported(1, s.D, s.L, layer->dtype == DD_BF16) ? prepared_bytes(s) : 0;
@@ -275,7 +282,7 @@ dd_status dd_bwd_weight(const dd_layer *layer, const void *X, const void *dY, co
     if (dd_status st = check_ws(ws, ws_bytes, dd_workspace_bytes(DD_OP_BWD_WEIGHT, layer, 0))) return st;
     bool matrix = wants_matrix_wgrad(layer, s);
     if (matrix && !(aligned16(X) && aligned16(dY))) matrix = false;  // 16-byte transfers into LDS
-    if ((layer->algo == DD_ALGO_MATRIX || layer->algo == DD_ALGO_PREPARED) && !matrix) return DD_ERR_UNSUPPORTED;
+    if (layer->algo != DD_ALGO_AUTO && layer->algo != DD_ALGO_VECTOR && !matrix) return DD_ERR_UNSUPPORTED;
     // the family that runs must fit the scratch that was checked (the two cut the tokens differently)
     const size_t runs_in = matrix ? dd::weight_grad_matrix_ws_bytes(layer->tokens, s.D, s.L, layer->K)
                                   : dd::weight_grad_vector_ws_bytes(layer->tokens, s.D, s.L, layer->K,

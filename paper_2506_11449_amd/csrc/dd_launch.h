@@ -65,6 +65,10 @@ hipError_t launch_product_vector(const ProductArgs &a, hipStream_t stream);
 bool product_matrix_supported(int64_t T, int D, int L, bool bf16);
 size_t product_matrix_ws_bytes(int D, int L);
 hipError_t launch_product_matrix(const ProductArgs &a, hipStream_t stream);
+// The same product on prepared operands, skipping the 32 x 16 operand blocks that no diagonal crosses (a.offsets says
+// which); one layer at a time (no groups), long side <= 8192.
+bool product_blocks_supported(int64_t T, int D, int L, bool bf16);
+hipError_t launch_product_blocks(const ProductArgs &a, hipStream_t stream);
 // Both dense operands of `sets` equally shaped layers (offsets [sets x K], values [sets x K x L]) in one launch:
 // the forward operands side by side at `forward_operand`, the backward-input operands stacked along the
 // contraction at `backward_operand`, sets * D * L elements each.

@@ -233,7 +233,7 @@ __device__ __forceinline__ void store_tile(uint16_t *__restrict__ C, const unsig
 
 template <int BM, int BN, int NW>
 __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int a_cols, int c_cols, int tiles_m,
-                                                        int tiles_n, const uint16_t *__restrict__ A,
+                                                        int tiles_n, int group_n, const uint16_t *__restrict__ A,
                                                         const uint16_t *__restrict__ Wf,
                                                         uint16_t *__restrict__ C)
 {
@@ -248,7 +248,9 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
     const int per_xcd = (n_tiles + kXcds - 1) / kXcds;
     const int lin = int(blockIdx.x % kXcds) * per_xcd + int(blockIdx.x / kXcds);
     if (lin >= n_tiles) return;
-    const int tm = lin / tiles_n, tn = lin % tiles_n;
+    // (column tiles in groups of group_n, see tile_group: all token blocks of one group before the next group)
+    const int vrow = lin / group_n, group = vrow / tiles_m;
+    const int tm = vrow - group * tiles_m, tn = group * group_n + lin % group_n;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -431,7 +433,8 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
 // ---------------------------------------------------------------------------------------------
 template <int BM, int BN, int NW>
 __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, int KD, int a_cols, int c_cols,
-                                                                  int tiles_m, int tiles_n,
+                                                                  int tiles_m, int tiles_n, int group_n,
+                                                                  unsigned tiles_m_magic,
                                                                   const uint16_t *__restrict__ A,
                                                                   const uint16_t *__restrict__ Wf,
                                                                   uint16_t *__restrict__ C)
@@ -444,6 +447,10 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
 
     // The tiles are cut into one contiguous run per XCD (column tiles innermost, so that tiles sharing a
     // token block run on the same L2); workgroup `slot` of an XCD takes every kSlots-th tile of its run.
+    // The order of the tiles is that of a matrix of group_n column tiles and tiles_m * (tiles_n / group_n) rows:
+    // row v of it is token block v mod tiles_m of column group v / tiles_m (see tile_group).  The cursors below walk
+    // that matrix; the token block and column tile a position stands for are kept beside it (one multiply-high by
+    // tiles_m_magic = ceil(2^32 / tiles_m) per move, on the scalar unit).
     const int n_tiles = tiles_m * tiles_n;
     const int per_xcd = (n_tiles + kXcds - 1) / kXcds;
     const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
@@ -493,23 +500,30 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
     struct Cursor {
         int tiles_left;  // my tiles after this one
         int kt;          // k-slice inside the tile
-        int tm, tn;      // the tile
+        int tm, tn;      // the tile's place in the grouped order: row and column of the matrix described above
         int set;         // matrix of the stack A that holds this slice
         int set_col;     // first contraction index of the slice inside that matrix
+        int rm, rn;      // the tile itself: token block and column tile
     };
-    const int hop_m = kSlots / tiles_n, hop_n = kSlots % tiles_n;  // from one of my tiles to the next
-    Cursor wc = {n_mine - 1, 0, first / tiles_n, first % tiles_n, 0, 0};
+    const int hop_m = kSlots / group_n, hop_n = kSlots % group_n;  // from one of my tiles to the next
+#define DD_REAL_M(v_) (int(v_) - int(__umulhi(unsigned(v_), tiles_m_magic)) * tiles_m)
+#define DD_REAL_N(v_, c_) (int(__umulhi(unsigned(v_), tiles_m_magic)) * group_n + (c_))
+    Cursor wc = {n_mine - 1, 0, first / group_n, first % group_n, 0, 0, 0, 0};
+    wc.rm = DD_REAL_M(wc.tm);
+    wc.rn = DD_REAL_N(wc.tm, wc.tn);
     Cursor xc = wc;
-    int out_tm = wc.tm, out_tn = wc.tn;  // the tile being multiplied
+    int out_tm = wc.tm, out_tn = wc.tn;  // the tile being multiplied (place in the grouped order)
 #define DD_ADVANCE(c_) /* selects only: a branch here would split the loop body */                      \
     {                                                                                                   \
         const int wrap = c_.kt + 1 == KT ? 1 : 0;                                                       \
         const int move = wrap & (c_.tiles_left > 0 ? 1 : 0);                                            \
-        const int carry = c_.tn + hop_n >= tiles_n ? 1 : 0;                                             \
+        const int carry = c_.tn + hop_n >= group_n ? 1 : 0;                                             \
         const int next_set = c_.set_col + kBK == a_cols ? 1 : 0;                                        \
-        const int tn1 = c_.tn + hop_n - carry * tiles_n, tm1 = c_.tm + hop_m + carry;                   \
+        const int tn1 = c_.tn + hop_n - carry * group_n, tm1 = c_.tm + hop_m + carry;                   \
         c_.tn = move ? tn1 : c_.tn;                                                                     \
         c_.tm = move ? tm1 : c_.tm;                                                                     \
+        c_.rm = DD_REAL_M(c_.tm);                                                                       \
+        c_.rn = DD_REAL_N(c_.tm, c_.tn);                                                                \
         c_.tiles_left -= move;                                                                          \
         c_.set = (c_.set + next_set) * (1 - wrap);                                                      \
         c_.set_col = (c_.set_col + kBK) * (1 - (wrap | next_set));                                      \
@@ -525,8 +539,8 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
     const size_t a_matrix = size_t(T) * a_cols;                    // from one matrix of the stack to the next
 #define DD_X_AT(n_)                                                                                     \
     (A + (size_t(xc.set) * a_matrix + xc.set_col + x_col[n_]) +                                         \
-     size_t(unsigned(min(xc.tm * BM + x_row[n_], T - 1))) * unsigned(a_cols))
-#define DD_W_AT(a_) (Wf + (size_t(wc.tn) * w_tile_step + size_t(wc.kt) * 4 * 512) + w_lane[a_])
+     size_t(unsigned(min(xc.rm * BM + x_row[n_], T - 1))) * unsigned(a_cols))
+#define DD_W_AT(a_) (Wf + (size_t(wc.rn) * w_tile_step + size_t(wc.kt) * 4 * 512) + w_lane[a_])
     const uint16_t *x_ptr[Tl::X_CHUNKS];  // where the next token slice to request starts, piece by piece
     const uint16_t *w_ptr[Tl::FA];        // where the next weight fragments to request start
 #define DD_LOAD_X(xg_) /* the slice under the cursor; the cursor moves on */                           \
@@ -621,18 +635,19 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
                     _Pragma("unroll") for (int i = 0; i < 4; ++i) acc[a][b][4 * q + i] = 0.f;           \
                 }                                                                                       \
         {                                                                                               \
-            int matrix = (out_tn * BN) / c_cols;                                                        \
-            int col = out_tn * BN - matrix * c_cols + out_piece * 8;                                    \
+            const int real_tm = DD_REAL_M(out_tm), real_tn = DD_REAL_N(out_tm, out_tn);                 \
+            int matrix = (real_tn * BN) / c_cols;                                                       \
+            int col = real_tn * BN - matrix * c_cols + out_piece * 8;                                   \
             _Pragma("unroll") for (int hop = 0; hop < 2; ++hop)                                         \
                 if (col >= c_cols) {                                                                    \
                     col -= c_cols;                                                                      \
                     ++matrix;                                                                           \
                 }                                                                                       \
-            parked_dst = C + (size_t(matrix) * T + size_t(out_tm) * BM) * c_cols + col;                 \
-            parked_rows = min(BM, T - out_tm * BM);                                                     \
+            parked_dst = C + (size_t(matrix) * T + size_t(real_tm) * BM) * c_cols + col;                \
+            parked_rows = min(BM, T - real_tm * BM);                                                    \
         }                                                                                               \
-        const bool carry = out_tn + hop_n >= tiles_n;                                                   \
-        out_tn += hop_n - (carry ? tiles_n : 0);                                                        \
+        const bool carry = out_tn + hop_n >= group_n;                                                   \
+        out_tn += hop_n - (carry ? group_n : 0);                                                        \
         out_tm += hop_m + (carry ? 1 : 0);                                                              \
     }
     // token tile b_ of the parked result -> LDS
@@ -696,6 +711,8 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
 #undef DD_STEP
 #undef DD_XF_ONE
 #undef DD_ADVANCE
+#undef DD_REAL_M
+#undef DD_REAL_N
 #undef DD_X_AT
 #undef DD_W_AT
 #undef DD_LOAD_X
@@ -716,6 +733,29 @@ bool product_matrix_supported(int64_t T, int D, int L, bool bf16)
 
 size_t product_matrix_ws_bytes(int D, int L) { return size_t(D) * size_t(L) * 2; }
 
+// Order of the result tiles.  A workgroup's column tile needs BN columns of the dense operand over the whole
+// contraction; the column tiles that run side by side on one XCD should find theirs in its 4 MB L2 together with
+// the token rows in flight.  Where the whole operand is too large for that (ViT MLP layers: 4.7 MB), the column
+// tiles are taken in groups whose operand slice fits, every token block of one group before the next group: the
+// token matrix is then fetched once per group instead of the operand once per round of tiles.  Returns the
+// number of column tiles per group (a divisor of tiles_n; tiles_n itself = plain order), by the fetches either
+// order costs.
+static int tile_group(int64_t tiles_m, int tiles_n, int BN, int KD)
+{
+    const double col_tile = double(BN) * KD * 2;               // operand bytes of one column tile
+    const double fits = 1.75 * 1024 * 1024;                    // what stays resident beside the streams
+    const double a_bytes = double(tiles_m) * 160 * KD * 2;     // token matrix (160-token blocks)
+    const double rounds = double(tiles_m) * tiles_n / (kXcds * 32);  // per XCD: every round streams what does not fit
+    int best = tiles_n;
+    double best_cost = a_bytes + kXcds * col_tile * tiles_n * (col_tile * tiles_n <= fits ? 1.0 : (rounds > 1 ? rounds : 1.0));
+    for (int g = tiles_n - 1; g >= 1; --g) {
+        if (tiles_n % g || col_tile * g > fits) continue;
+        const double cost = a_bytes * (tiles_n / g) + kXcds * col_tile * tiles_n;
+        if (cost < best_cost) { best_cost = cost; best = g; }
+    }
+    return best;
+}
+
 template <int BM, int BN, int NW>
 static hipError_t launch_mm(int T, int NC, int KD, int a_cols, int c_cols, const uint16_t *A, const uint16_t *Wf,
                             uint16_t *C, hipStream_t stream)
@@ -726,7 +766,7 @@ static hipError_t launch_mm(int T, int NC, int KD, int a_cols, int c_cols, const
     const int tiles_m = (T + BM - 1) / BM, tiles_n = NC / BN;
     const int per_xcd = (tiles_m * tiles_n + kXcds - 1) / kXcds;
     hipLaunchKernelGGL((mm_kernel<BM, BN, NW>), dim3(per_xcd * kXcds), dim3(Tl::THREADS), Tl::LDS_BYTES, stream, T, NC, KD,
-                       a_cols, c_cols, tiles_m, tiles_n, A, Wf, C);
+                       a_cols, c_cols, tiles_m, tiles_n, tiles_n, A, Wf, C);  // every tile is resident at once: plain order
     return hipGetLastError();
 }
 
@@ -789,8 +829,13 @@ static hipError_t launch_mm_persistent(int T, int NC, int KD, int a_cols, int c_
     static std::atomic<uint64_t> lds_allowed{0};  // one bit per device
     if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&mm_persistent_kernel<BM, BN, NW>), kLds, lds_allowed)) return e;
     const int tiles_m = (T + BM - 1) / BM, tiles_n = NC / BN;
+    int group_n = tile_group(tiles_m, tiles_n, BN, KD);
+    // rows of the grouped order are divided by tiles_m with one multiply-high: exact while rows * tiles_m < 2^32;
+    // in the plain order the quotient is always 0, which a multiplier of 0 gives for any size
+    if (uint64_t(tiles_m) * tiles_m * (tiles_n / group_n) >= (uint64_t(1) << 32)) group_n = tiles_n;
+    const unsigned magic = group_n == tiles_n ? 0u : unsigned(((uint64_t(1) << 32) + tiles_m - 1) / tiles_m);
     hipLaunchKernelGGL((mm_persistent_kernel<BM, BN, NW>), dim3(256), dim3(Tl::THREADS), kLds, stream, T, NC, KD,
-                       a_cols, c_cols, tiles_m, tiles_n, A, Wf, C);
+                       a_cols, c_cols, tiles_m, tiles_n, group_n, magic, A, Wf, C);
     return hipGetLastError();
 }
 

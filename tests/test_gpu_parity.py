@@ -452,3 +452,45 @@ def test_weight_gradient_misaligned_inputs_stay_inside_the_workspace(M, N, K, T)
         st = lib.dd_bwd_weight(ctypes.byref(lm), vp(d_X.data_ptr()), vp(d_dY.data_ptr()), vp(d_off.data_ptr()),
                                vp(dV.data_ptr()), vp(ws.data_ptr()), need + guard, stream)
         assert st == 2
+
+
+BLOCKS = [(768, 768, 77, 2, 300), (768, 768, 77, 5, 1290), (768, 768, 77, 0, 517), (384, 1152, 115, 4, 333),
+          (1152, 384, 60, 7, 333), (768, 3072, 307, 3, 700), (3072, 768, 307, 3, 257), (128, 128, 13, 1, 1),
+          (1024, 1024, 51, 0, 600), (256, 8192, 100, 2, 70), (8192, 256, 100, 2, 70), (512, 512, 512, 0, 90)]
+
+
+@pytest.mark.parametrize("M,N,K,bands,T", BLOCKS)
+def test_block_skipping_products(M, N, K, bands, T):
+    """DD_ALGO_BLOCKS: the products on prepared operands that skip every 32 x 16 operand block no diagonal crosses.
+    Clustered offsets (runs of adjacent diagonals, some wrapping), uniform ones (nothing to skip) and the dense case;
+    both orientations, ragged token counts; against the oracle, and against the kernel that skips nothing."""
+    D = max(M, N)
+    offsets = (synth.draw_offsets_clustered(D, K, bands, seed=M + N + bands) if bands
+               else synth.draw_offsets(D, K, seed=M + N))
+    _, values, X, dY = random_case(M, N, K, T, "bf16", seed=K + T, offsets=offsets)
+    d_off, d_val = torch.from_numpy(offsets).cuda(), to_dev(values, "bf16")
+    d_X, d_dY = to_dev(X, "bf16"), to_dev(dY, "bf16")
+    prepared = dd.dd_prepare(d_off, d_val, M, N)
+    Y = dd.dd_fwd(d_X, d_off, None, N, prepared=prepared, algo=dd.DD_ALGO_BLOCKS)
+    dX = dd.dd_bwd_input(d_dY, d_off, None, M, prepared=prepared, algo=dd.DD_ALGO_BLOCKS)
+    Y2 = dd.dd_fwd(d_X, None, None, N, prepared=prepared)
+    dX2 = dd.dd_bwd_input(d_dY, None, None, M, prepared=prepared)
+    torch.cuda.synchronize()
+    assert rel_err(to_host(Y), orc.fwd(X, offsets, values, N)) <= TOL["bf16"]
+    assert rel_err(to_host(dX), orc.bwd_input(dY, offsets, values, M)) <= TOL["bf16"]
+    # a skipped block holds zeros only, so both kernels add the same products; they may round the fp32 sums differently
+    assert rel_err(to_host(Y), to_host(Y2)) <= 2.0 ** -8
+    assert rel_err(to_host(dX), to_host(dX2)) <= 2.0 ** -8
+
+
+def test_block_skipping_needs_offsets_and_a_prepared_block():
+    import ctypes
+    lib = dd.load_library()
+    l = dd.make_layer(64, 768, 768, 77, torch.bfloat16, dd.DD_ALGO_BLOCKS)
+    one = ctypes.c_void_p(256)  # never dereferenced: refused on the host
+    need = dd.dd_workspace_bytes(dd.DD_OP_FWD, l)
+    assert need == 2 * 768 * 768 * 2
+    assert lib.dd_fwd(ctypes.byref(l), one, None, None, one, one, need, None) == 1      # no offsets
+    assert lib.dd_fwd(ctypes.byref(l), one, one, None, one, one, need - 1, None) == 3   # block too small
+    l32 = dd.make_layer(64, 768, 768, 77, torch.float32, dd.DD_ALGO_BLOCKS)
+    assert lib.dd_fwd(ctypes.byref(l32), one, one, None, one, one, need, None) == 2     # fp32 storage
