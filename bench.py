@@ -267,6 +267,17 @@ class LayerBench:
             if self.D <= 8192:
                 us["dd_fwd_blocks"] = time_loop(torch, self.fwd_blocks, n) * 1e3
                 us["dd_bwd_input_blocks"] = time_loop(torch, self.bwd_input_blocks, n) * 1e3
+        # What reading dY once for both backward products could save at most: the same calls on ONE buffer set, so that
+        # whatever the caches can hold of X and dY is served from them (at 12608 tokens everything fits the 256 MB
+        # memory-side cache), and the two products of one layer back to back on the same dY, as a training step
+        # issues them (the second then finds dY where the first left it).
+        us["cache_hot"] = {"dd_bwd_input": time_loop(torch, lambda i: self.bwd_input(0), n) * 1e3,
+                           "dd_bwd_weight": time_loop(torch, lambda i: self.bwd_weight(0), n) * 1e3}
+
+        def pair(i):
+            self.bwd_input(i)
+            self.bwd_weight(i)
+        us["dd_bwd_input+dd_bwd_weight_same_dY"] = time_loop(torch, pair, n) * 1e3
         line = {"layer": f"{self.M}->{self.N}", "tokens": self.T, "K": self.K, "dtype": self.layer.dtype,
                 "buffer_sets": self.S, "us": us,
                 "sparse_tflops": {k: self.flops() / us[k] / 1e6 for k in ("dd_fwd", "dd_bwd_input", "dd_bwd_weight")},

@@ -31,7 +31,8 @@
  *     products: max(M, N) > 65535, or DD_ALGO_MATRIX / DD_ALGO_PREPARED forced where the matrix-core
  *     kernels do not apply.  They cover bf16 storage, 16-byte aligned matrices and M, N both multiples
  *     of 128 (dd_bwd_weight: both multiples of 192, or both of 128), max(M, N) <= 8192; DD_ALGO_AUTO
- *     takes them there when K / max(M, N) >= 1/48 and the vector kernels everywhere else -- also for a matrix
+ *     takes them there at every density (they are faster than the vector kernels from K = 1 on) and the vector
+ *     kernels everywhere else -- also for a matrix
  *     that is not 16-byte aligned (a view that starts at an odd element): such a call is legal under DD_ALGO_AUTO
  *     and several times slower; DD_ALGO_MATRIX / DD_ALGO_PREPARED report it as DD_ERR_UNSUPPORTED instead.
  *     DD_ERR_HIP: the launch itself failed.

@@ -47,16 +47,17 @@ size_t select_ws_bytes(int32_t, int32_t, int32_t) { return 0; }
 
 bool aligned16(const void *p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
 
-// Does the shape allow the matrix-core kernels, and does the request (or the density) ask for them?
-// Below a density K/D of about 1/48 visiting only the stored weights on the vector ALUs is cheaper
-// than a dense contraction on the matrix cores (their rates differ by 32x, less what tiling loses).
+// Does the shape allow the matrix-core kernels?  Then every request but DD_ALGO_VECTOR runs them.  The dense
+// contraction costs the same whatever K is and the vector kernels cost in proportion to K, but measured over K = 1 ...
+// D/8 (`bench.py --k-sweep`; 768^2 at 12608 tokens: 23.6 us against 55.8 us at K = 1, 24.3 against 123 at K = 96;
+// 1024^2 at 25216 tokens: 66 against 229 at K = 1) the matrix cores win at every density, because the vector kernels'
+// cost of moving a tile through LDS alone exceeds the whole dense product; so DD_ALGO_AUTO has no density threshold.
 bool wants_matrix(const dd_layer *l, const Shape &s)
 {
     if (l->algo == DD_ALGO_VECTOR) return false;
     // (a call without tokens launches nothing, whatever the family)
     if (!dd::product_matrix_supported(l->tokens > 0 ? l->tokens : 1, s.D, s.L, l->dtype == DD_BF16)) return false;
-    return l->algo == DD_ALGO_MATRIX || l->algo == DD_ALGO_PREPARED || l->algo == DD_ALGO_BLOCKS ||
-           int64_t(l->K) * 48 >= s.D;
+    return true;
 }
 
 // the block dd_prepare fills: the operand of the forward product, then the one of the backward-input product
@@ -66,8 +67,7 @@ bool wants_matrix_wgrad(const dd_layer *l, const Shape &s)
 {
     if (l->algo == DD_ALGO_VECTOR) return false;
     if (!dd::weight_grad_matrix_supported(l->tokens, s.D, s.L, l->dtype == DD_BF16)) return false;
-    return l->algo == DD_ALGO_MATRIX || l->algo == DD_ALGO_PREPARED || l->algo == DD_ALGO_BLOCKS ||
-           int64_t(l->K) * 48 >= s.D;
+    return true;
 }
 
 // Scratch of dd_bwd_weight.  A forced matrix-core call runs those kernels or fails, so it needs their partial
