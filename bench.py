@@ -296,6 +296,48 @@ class LayerBench:
         return line
 
 
+def helper_paths(b, n):
+    """The differentiable selection (Sec. 3.2 Eq. 4-5) and the heuristic update of the active set beside one layer's
+    step: step by step, and folded into the launches of the layer's own path.  us per call."""
+    torch, dd = b.torch, b.dd
+    K, D = b.K, b.D
+    at = dd.dd_soft_topk(b.scores, K, 1.0)
+    V = b.values.clone()
+    eff = torch.empty_like(V)
+    dsc_in = torch.randn((1, D), device="cuda")
+    t = lambda fn: time_loop(torch, fn, n) * 1e3
+    steps = {"dd_soft_topk": t(lambda i: dd.dd_soft_topk(b.scores, K, 1.0, alpha_tilde=at)),
+             "dd_scale_values": t(lambda i: dd.dd_scale_values(b.off[0], at[0], V, values_eff=eff)),
+             "dd_scale_values_bwd": t(lambda i: dd.dd_scale_values_bwd(b.off[0], at[0], V, b.dV, ws=b.ws)),
+             "dd_soft_topk_bwd": t(lambda i: dd.dd_soft_topk_bwd(b.scores, K, 1.0, dsc_in))}
+    out = {"step_by_step": steps, "step_by_step_sum": sum(steps.values())}
+    if b.use_prepare:
+        dV2 = torch.empty_like(b.dV)
+        dat = torch.empty(D, device="cuda")
+        prep = dd.dd_prepare_scaled(b.off[0], at[0], V, b.M, b.N)
+        fused = {"dd_select_soft": t(lambda i: dd.dd_select_soft(b.scores, K, 1.0, offsets_out=b.off, alpha_tilde=at)),
+                 "dd_select_diagonals": t(b.select),
+                 "dd_prepare_scaled": t(lambda i: dd.dd_prepare_scaled(b.off[0], at[0], V, b.M, b.N, prepared=prep)),
+                 "dd_prepare": t(b.prepare),
+                 "dd_bwd_weight_scaled": t(lambda i: dd.dd_bwd_weight_scaled(b.X[i % b.S], b.dY[i % b.S], b.off[0], at[0],
+                                                                             V, dV=dV2, d_alpha_tilde=dat, ws=b.ws)),
+                 "dd_bwd_weight": t(b.bwd_weight)}
+        out["folded_into_the_path"] = fused
+        out["folded_extra_over_the_plain_path"] = (fused["dd_select_soft"] - fused["dd_select_diagonals"] +
+                                                   fused["dd_prepare_scaled"] - fused["dd_prepare"] +
+                                                   fused["dd_bwd_weight_scaled"] - fused["dd_bwd_weight"] +
+                                                   steps["dd_soft_topk_bwd"])
+    rnd = torch.rand(D, device="cuda")
+    mag = dd.dd_diag_magnitude(b.values)
+    n_drop = max(1, (3 * K) // 10)  # RigL's initial drop fraction
+    out["diagheur"] = {"dd_diag_magnitude": t(lambda i: dd.dd_diag_magnitude(b.values, magnitudes=mag)),
+                       "dd_diagheur_update": t(lambda i: dd.dd_diagheur_update(D, b.off[0], mag, rnd, n_drop, ws=b.ws))}
+    b.select(0)
+    if b.use_prepare:
+        b.prepare(0)
+    return out
+
+
 def cpu_baseline_layers(layers, token_slice, scale, what, synth):
     """The oracle, as it stands, on the host cores over `token_slice` tokens of each layer; scaled to the step."""
     from oracle import dd_oracle as orc
@@ -503,6 +545,8 @@ def run_layers(args, torch, dd, synth, dense, workload):
     value = 3 * flops / (ms_per_step * 1e-3) / 1e12
     n = max(20, min(steps, 100))
     lines = [b.measure(n, dense) for b in benches]
+    if workload == "vitb_attn_proj":
+        lines[0]["selection_helpers_us"] = helper_paths(benches[0], n)
     e = 2 if layers[0].dtype == "bf16" else 4
     per = {k: sum(l["us"][k] for l in lines) * 1e-6 for k in ("dd_fwd", "dd_bwd_input", "dd_bwd_weight")}
     dominant = max(per, key=per.get)
@@ -543,6 +587,8 @@ def config_sublines(args, torch, dd, synth, dense):
         for i, l in enumerate(distinct(synth.WORKLOADS[name])):
             b = LayerBench(torch, dd, synth, l, "auto", 0, 0, seed=2506 + i)
             lines.append(b.measure(30 if l.tokens < 20000 else 15, dense))
+            if name == "vitb_attn_proj":
+                lines[-1]["selection_helpers_us"] = helper_paths(b, 30)
             del b
             torch.cuda.empty_cache()
         out[name] = lines

@@ -80,7 +80,8 @@ typedef enum {
     DD_OP_SELECT = 3,
     DD_OP_SCALE_VALUES_BWD = 4, /* layer->K diagonals: scratch of dd_scale_values_bwd */
     DD_OP_PREPARE = 5,          /* the block dd_prepare fills and DD_ALGO_PREPARED calls read */
-    DD_OP_DIAGHEUR = 6          /* layer->in_features candidates, layer->K diagonals: scratch of dd_diagheur_update */
+    DD_OP_DIAGHEUR = 6,         /* layer->in_features candidates, layer->K diagonals: scratch of dd_diagheur_update */
+    DD_OP_BWD_WEIGHT_SCALED = 7 /* scratch of dd_bwd_weight_scaled (0 where it returns DD_ERR_UNSUPPORTED) */
 } dd_op;
 
 typedef struct {
@@ -235,6 +236,34 @@ dd_status dd_select_diagonals(int32_t batch, int32_t D, int32_t K, const float *
  */
 dd_status dd_soft_topk(int32_t batch, int32_t D, int32_t K, float temperature, const float *scores,
                        float *alpha_tilde, void *hip_stream);
+
+/*
+ * The differentiable selection of Sec. 3.2 with its steps folded into the launches of the layer's own path (the
+ * four calls above and below remain for callers that want the steps one by one; results agree as stated):
+ *
+ * dd_select_soft       dd_select_diagonals and dd_soft_topk on the same score vectors in one launch (Eq. 4 picks the K
+ *                      diagonals, Eq. 5 weighs the D candidates).  offsets_out [batch x K] and alpha_tilde [batch x D]
+ *                      are bit for bit those of the two calls.  Errors as for the two calls.
+ * dd_prepare_scaled    dd_prepare on the effective values alpha_tilde[o_k] * V[k] (Eq. 4), formed while the dense
+ *                      operands are built: no values_eff array is written or read.  alpha_tilde [D] fp32, V [K x L]
+ *                      dtype; the block is bit for bit what dd_scale_values followed by dd_prepare builds.
+ * dd_bwd_weight_scaled dd_bwd_weight followed by dd_scale_values_bwd, the adjoint of the scaling being the epilogue of
+ *                      the weight gradient's ordered sum over the token chunks (no dValues array in between, two
+ *                      launches instead of four):  dV[k][p] = alpha_tilde[o_k] * dValues[k][p]  [K x L] fp32 (bit for
+ *                      bit as the two calls), d_alpha_tilde[i] = sum over the diagonals with o_k = i of
+ *                      <dValues[k], V[k]>  [D] fp32 (0 elsewhere; within 1e-5, the dot products are summed in another
+ *                      order).  An offset given three times or more: the order of those fp32 additions is unspecified.
+ *                      ws: dd_workspace_bytes(DD_OP_BWD_WEIGHT_SCALED, layer, 0).  Matrix-core kernels only:
+ *                      DD_ERR_UNSUPPORTED for fp32 storage, shapes dd_bwd_weight's matrix-core kernels do not cover,
+ *                      X or dY not 16-byte aligned, DD_ALGO_VECTOR, tokens = 0 -- call the two steps there.
+ */
+dd_status dd_select_soft(int32_t batch, int32_t D, int32_t K, float temperature, const float *scores,
+                         int32_t *offsets_out, float *alpha_tilde, void *hip_stream);
+dd_status dd_prepare_scaled(const dd_layer *layer, const int32_t *offsets, const float *alpha_tilde, const void *V,
+                            void *prepared, size_t prepared_bytes, void *hip_stream);
+dd_status dd_bwd_weight_scaled(const dd_layer *layer, const void *X, const void *dY, const int32_t *offsets,
+                               const float *alpha_tilde, const void *V, float *dV, float *d_alpha_tilde, void *ws,
+                               size_t ws_bytes, void *hip_stream);
 
 /*
  * Derivative of dd_soft_topk: d_scores [batch x D] from d_alpha_tilde [batch x D] (both fp32); entries

@@ -14,11 +14,11 @@ from .build import LIB_PATH
 DD_F32, DD_BF16 = 0, 1
 DD_ALGO_AUTO, DD_ALGO_VECTOR, DD_ALGO_MATRIX, DD_ALGO_PREPARED, DD_ALGO_BLOCKS = 0, 1, 2, 3, 4
 DD_OP_FWD, DD_OP_BWD_INPUT, DD_OP_BWD_WEIGHT, DD_OP_SELECT, DD_OP_SCALE_VALUES_BWD, DD_OP_PREPARE = 0, 1, 2, 3, 4, 5
-DD_OP_DIAGHEUR = 6
+DD_OP_DIAGHEUR, DD_OP_BWD_WEIGHT_SCALED = 6, 7
 
 EXPORTS = ("dd_workspace_bytes", "dd_fwd", "dd_prepare", "dd_prepare_batched", "dd_select_prepare", "dd_prepare_shared", "dd_fwd_shared", "dd_bwd_input_shared",
            "dd_bwd_input", "dd_bwd_weight", "dd_bwd_weight_static", "dd_static_scratch_bytes", "dd_select_diagonals",
-           "dd_soft_topk", "dd_soft_topk_bwd", "dd_scale_values", "dd_scale_values_bwd", "dd_diag_magnitude",
+           "dd_select_soft", "dd_prepare_scaled", "dd_bwd_weight_scaled", "dd_soft_topk", "dd_soft_topk_bwd", "dd_scale_values", "dd_scale_values_bwd", "dd_diag_magnitude",
            "dd_diagheur_update", "dd_status_string")
 
 
@@ -64,6 +64,9 @@ def load_library():
     lib.dd_static_scratch_bytes.restype = sz
     lib.dd_select_diagonals.argtypes = [i32, i32, i32, vp, vp, vp, sz, vp]
     f32 = ctypes.c_float
+    lib.dd_select_soft.argtypes = [i32, i32, i32, f32, vp, vp, vp, vp]
+    lib.dd_prepare_scaled.argtypes = [lp, vp, vp, vp, vp, sz, vp]
+    lib.dd_bwd_weight_scaled.argtypes = [lp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.dd_soft_topk.argtypes = [i32, i32, i32, f32, vp, vp, vp]
     lib.dd_soft_topk_bwd.argtypes = [i32, i32, i32, f32, vp, vp, vp, vp]
     lib.dd_scale_values.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp]
@@ -361,6 +364,61 @@ def dd_select_diagonals(scores, K, offsets_out=None, ws=None, stream=None):
     wp, wn = _ws_for(need, scores.device, ws)
     _check(_lib.dd_select_diagonals(B, D, int(K), _ptr(scores), _ptr(offsets_out), wp, wn, _stream(stream)))
     return offsets_out
+
+
+def dd_select_soft(scores, K, temperature, offsets_out=None, alpha_tilde=None, stream=None):
+    """dd_select_diagonals and dd_soft_topk in one launch: (offsets int32 [batch x K], alpha_tilde fp32 [batch x D])."""
+    B, D = scores.shape
+    _dev(scores, torch.float32, (B, D), "scores")
+    if offsets_out is None:
+        offsets_out = torch.empty((B, K), dtype=torch.int32, device=scores.device)
+    if alpha_tilde is None:
+        alpha_tilde = torch.empty_like(scores)
+    _dev(offsets_out, torch.int32, (B, K), "offsets_out")
+    _dev(alpha_tilde, torch.float32, (B, D), "alpha_tilde")
+    _check(load_library().dd_select_soft(B, D, int(K), float(temperature), _ptr(scores), _ptr(offsets_out),
+                                         _ptr(alpha_tilde), _stream(stream)))
+    return offsets_out, alpha_tilde
+
+
+def dd_prepare_scaled(offsets, alpha_tilde, V, in_features, out_features, prepared=None, stream=None):
+    """dd_prepare on alpha_tilde[o_k] * V[k] without writing the scaled values anywhere."""
+    M, N, K = int(in_features), int(out_features), offsets.shape[0]
+    _, ref, need = _plan(DD_OP_PREPARE, 0, M, N, K, V.dtype, DD_ALGO_PREPARED)
+    _dev(offsets, torch.int32, (K,), "offsets")
+    _dev(alpha_tilde, torch.float32, (max(M, N),), "alpha_tilde")
+    _dev(V, V.dtype, (K, min(M, N)), "V")
+    if prepared is None:
+        prepared = Prepared(torch.empty(max(need, 1), dtype=torch.uint8, device=V.device), M, N, K, V.dtype)
+    if (prepared.in_features, prepared.out_features, prepared.K, prepared.dtype) != (M, N, K, V.dtype):
+        raise ValueError("prepared block belongs to another layer")
+    _check(load_library().dd_prepare_scaled(ref, _ptr(offsets), _ptr(alpha_tilde), _ptr(V), _ptr(prepared.buf),
+                                            prepared.buf.numel(), _stream(stream)))
+    return prepared
+
+
+def dd_bwd_weight_scaled(X, dY, offsets, alpha_tilde, V, dV=None, d_alpha_tilde=None, algo=DD_ALGO_AUTO, ws=None,
+                         stream=None):
+    """dd_bwd_weight and dd_scale_values_bwd as one call: (dV [K x L] fp32, d_alpha_tilde [D] fp32)."""
+    T, M = X.shape
+    N = dY.shape[1]
+    K, D, L = offsets.shape[0], max(M, N), min(M, N)
+    _, ref, need = _plan(DD_OP_BWD_WEIGHT_SCALED, T, M, N, K, X.dtype, algo)
+    _dev(X, X.dtype, (T, M), "X")
+    _dev(dY, X.dtype, (T, N), "dY")
+    _dev(offsets, torch.int32, (K,), "offsets")
+    _dev(alpha_tilde, torch.float32, (D,), "alpha_tilde")
+    _dev(V, X.dtype, (K, L), "V")
+    if dV is None:
+        dV = torch.empty((K, L), dtype=torch.float32, device=X.device)
+    if d_alpha_tilde is None:
+        d_alpha_tilde = torch.empty((D,), dtype=torch.float32, device=X.device)
+    _dev(dV, torch.float32, (K, L), "dV")
+    _dev(d_alpha_tilde, torch.float32, (D,), "d_alpha_tilde")
+    wp, wn = _ws_for(need, X.device, ws)
+    _check(load_library().dd_bwd_weight_scaled(ref, _ptr(X), _ptr(dY), _ptr(offsets), _ptr(alpha_tilde), _ptr(V),
+                                               _ptr(dV), _ptr(d_alpha_tilde), wp, wn, _stream(stream)))
+    return dV, d_alpha_tilde
 
 
 def dd_soft_topk(scores, K, temperature, alpha_tilde=None, stream=None):

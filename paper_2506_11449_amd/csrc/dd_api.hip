@@ -155,6 +155,11 @@ size_t dd_workspace_bytes(int op, const dd_layer *layer, int32_t batch)
         return dd::product_matrix_supported(1, s.D, s.L, layer->dtype == DD_BF16) ? prepared_bytes(s) : 0;
     case DD_OP_BWD_WEIGHT:
         return weight_grad_ws_bytes(layer, s);
+    case DD_OP_BWD_WEIGHT_SCALED: {
+        if (layer->algo == DD_ALGO_VECTOR || !wants_matrix_wgrad(layer, s)) return 0;
+        const size_t partials = dd::weight_grad_matrix_ws_bytes(layer->tokens, s.D, s.L, layer->K);
+        return (partials + kWsAlign - 1) / kWsAlign * kWsAlign + dd::weight_grad_scaled_tail_bytes(s.L, layer->K);
+    }
     default:
         return 0;
     }
@@ -302,6 +307,65 @@ dd_status dd_bwd_weight(const dd_layer *layer, const void *X, const void *dY, co
     a.ws = ws;
     const hipError_t e = matrix ? dd::launch_weight_grad_matrix(a, static_cast<hipStream_t>(hip_stream))
                                 : dd::launch_weight_grad_vector(a, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? DD_OK : DD_ERR_HIP;
+}
+
+dd_status dd_select_soft(int32_t batch, int32_t D, int32_t K, float temperature, const float *scores,
+                         int32_t *offsets_out, float *alpha_tilde, void *hip_stream)
+{
+    if (batch < 0 || D < 1 || K < 1 || K > D || !(temperature > 0.f)) return DD_ERR_INVALID_ARG;
+    if (D > 65536) return DD_ERR_UNSUPPORTED;
+    if (batch == 0) return DD_OK;
+    if (!scores || !offsets_out || !alpha_tilde) return DD_ERR_INVALID_ARG;
+    return dd::launch_select_soft(batch, D, K, temperature, scores, offsets_out, alpha_tilde,
+                                  static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? DD_OK
+               : DD_ERR_HIP;
+}
+
+dd_status dd_prepare_scaled(const dd_layer *layer, const int32_t *offsets, const float *alpha_tilde, const void *V,
+                            void *prepared, size_t prepared_bytes_given, void *hip_stream)
+{
+    Shape s;
+    if (dd_status st = check_layer(layer, &s)) return st;
+    if (!offsets || !alpha_tilde || !V) return DD_ERR_INVALID_ARG;
+    if (layer->algo == DD_ALGO_VECTOR) return DD_ERR_UNSUPPORTED;
+    if (!dd::product_matrix_supported(1, s.D, s.L, layer->dtype == DD_BF16)) return DD_ERR_UNSUPPORTED;
+    if (dd_status st = check_ws(prepared, prepared_bytes_given, prepared_bytes(s))) return st;
+    unsigned char *first = static_cast<unsigned char *>(prepared);
+    const hipError_t e = dd::launch_prepare_matrix(s.D, s.L, layer->K, 1, s.expanding, offsets, V, first,
+                                                   first + dd::product_matrix_ws_bytes(s.D, s.L),
+                                                   static_cast<hipStream_t>(hip_stream), alpha_tilde);
+    return e == hipSuccess ? DD_OK : DD_ERR_HIP;
+}
+
+dd_status dd_bwd_weight_scaled(const dd_layer *layer, const void *X, const void *dY, const int32_t *offsets,
+                               const float *alpha_tilde, const void *V, float *dV, float *d_alpha_tilde, void *ws,
+                               size_t ws_bytes, void *hip_stream)
+{
+    Shape s;
+    if (dd_status st = check_layer(layer, &s)) return st;
+    if (!offsets || !alpha_tilde || !V || !dV || !d_alpha_tilde) return DD_ERR_INVALID_ARG;
+    if (layer->tokens < 1 || !X || !dY) return DD_ERR_INVALID_ARG;
+    if (layer->algo == DD_ALGO_VECTOR || !wants_matrix_wgrad(layer, s) || !(aligned16(X) && aligned16(dY)))
+        return DD_ERR_UNSUPPORTED;  // elsewhere: dd_bwd_weight, then dd_scale_values_bwd
+    const size_t partials = dd::weight_grad_matrix_ws_bytes(layer->tokens, s.D, s.L, layer->K);
+    const size_t partials_padded = (partials + kWsAlign - 1) / kWsAlign * kWsAlign;
+    if (dd_status st = check_ws(ws, ws_bytes, partials_padded + dd::weight_grad_scaled_tail_bytes(s.L, layer->K))) return st;
+    dd::WeightGradArgs a;
+    a.T = layer->tokens;
+    a.D = s.D;
+    a.L = s.L;
+    a.K = layer->K;
+    a.bf16 = true;
+    a.A = s.expanding ? X : dY;
+    a.B = s.expanding ? dY : X;
+    a.offsets = offsets;
+    a.dValues = dV;
+    a.ws = ws;
+    const hipError_t e = dd::launch_weight_grad_matrix_scaled(a, alpha_tilde, V, d_alpha_tilde,
+                                                              static_cast<unsigned char *>(ws) + partials_padded,
+                                                              static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? DD_OK : DD_ERR_HIP;
 }
 

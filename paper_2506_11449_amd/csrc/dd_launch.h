@@ -72,9 +72,10 @@ hipError_t launch_product_blocks(const ProductArgs &a, hipStream_t stream);
 // Both dense operands of `sets` equally shaped layers (offsets [sets x K], values [sets x K x L]) in one launch:
 // the forward operands side by side at `forward_operand`, the backward-input operands stacked along the
 // contraction at `backward_operand`, sets * D * L elements each.
+// alpha (or null): importance weights of the D candidates; diagonal k enters as bf16(alpha[o_k] * values[k]).
 hipError_t launch_prepare_matrix(int D, int L, int K, int sets, bool expanding, const int32_t *offsets,
                                  const void *values, void *forward_operand, void *backward_operand,
-                                 hipStream_t stream);
+                                 hipStream_t stream, const float *alpha = nullptr);
 // The operands of `layers` independent layers of one shape in one launch (offsets [layers x K], values
 // [layers x K x L]): layer i's block, laid out as launch_prepare_matrix lays out a single layer (forward operand,
 // then backward-input operand), starts 2 * D * L elements after layer i-1's.
@@ -98,8 +99,17 @@ hipError_t launch_weight_grad_dot2_partials(const WeightGradArgs &a, hipStream_t
 bool weight_grad_matrix_supported(int64_t T, int D, int L, bool bf16);
 size_t weight_grad_matrix_ws_bytes(int64_t T, int D, int L, int K);
 hipError_t launch_weight_grad_matrix(const WeightGradArgs &a, hipStream_t stream);
+// The same with the adjoint of the scaling by the importance weights (Sec. 3.2 Eq. 4) as the epilogue of the ordered
+// sum over the token chunks: dV[k][p] = alpha[o_k] * dValues[k][p] (to a.dValues) and dalpha[i] = sum over the
+// diagonals with offset i of <dValues[k], V[k]>.  tail: scratch behind the partial sums, weight_grad_scaled_tail_bytes.
+size_t weight_grad_scaled_tail_bytes(int L, int K);
+hipError_t launch_weight_grad_matrix_scaled(const WeightGradArgs &a, const float *alpha, const void *V, float *dalpha,
+                                            void *tail, hipStream_t stream);
 
 hipError_t launch_select(int batch, int D, int K, const float *scores, int *out, hipStream_t stream);
+// selection and soft TopK weights of the same score vectors in one launch
+hipError_t launch_select_soft(int batch, int D, int K, float temperature, const float *scores, int *out,
+                              float *alpha_tilde, hipStream_t stream);
 
 // soft TopK weights and the scaling of the diagonals by them
 hipError_t launch_soft_topk(int batch, int D, int K, float temperature, const float *scores, float *alpha_tilde,

@@ -63,7 +63,8 @@ struct OperandPlace {
 //   gather:         row r = p in [0, L), KD = D:  w[q] = sum_{k: (p + o_k) mod D = q} v_k[p]
 // The first `masked_rows` workgroups build rows of the masked-gather operand, the others rows of the
 // gather operand (either count may be zero).  A row is summed in fp32 in LDS (repeated offsets add, Eq. 3)
-// and rounded to bf16 once.
+// and rounded to bf16 once.  alpha (or null): importance weights of the D candidates (Sec. 3.2 Eq. 4); diagonal k then
+// enters as alpha[o_k] * values[k], rounded to bf16 first -- exactly the values dd_scale_values would have stored.
 // blockIdx.y numbers the sets of a group of layers of one shape whose operands are stacked into one matrix
 // (set s uses offsets + s*K and values + s*K*L): an OperandPlace says where set s goes, s*col_step columns
 // to the right (the sets' outputs side by side) or s*k_step contraction indices down (their results summed),
@@ -75,7 +76,8 @@ __global__ __launch_bounds__(256) void materialize_kernel(int D, int L, int K, i
                                                           const uint16_t *__restrict__ values,
                                                           uint16_t *__restrict__ Wf_masked,
                                                           uint16_t *__restrict__ Wf_gather, OperandPlace place_masked,
-                                                          OperandPlace place_gather)
+                                                          OperandPlace place_gather,
+                                                          const float *__restrict__ alpha)
 {
     extern __shared__ float row[];
     const bool long_major = int(blockIdx.x) < masked_rows;
@@ -90,14 +92,16 @@ __global__ __launch_bounds__(256) void materialize_kernel(int D, int L, int K, i
     __syncthreads();
     for (int k = threadIdx.x; k < K; k += 256) {
         const int o = canonical_offset(offsets[k], D);
+        const int p = long_major ? (r - o < 0 ? r - o + D : r - o) : r;  // position along the diagonal
+        if (p >= L) continue;
+        float v = bf16_to_f32(values[size_t(k) * L + p]);
+        if (alpha) v = bf16_to_f32(f32_to_bf16(alpha[o] * v));
         if (long_major) {
-            int p = r - o;
-            if (p < 0) p += D;
-            if (p < L) atomicAdd(&row[p], bf16_to_f32(values[size_t(k) * L + p]));
+            atomicAdd(&row[p], v);
         } else {
             int q = r + o;
             if (q >= D) q -= D;
-            atomicAdd(&row[q], bf16_to_f32(values[size_t(k) * L + r]));
+            atomicAdd(&row[q], v);
         }
     }
     __syncthreads();
@@ -771,7 +775,8 @@ static hipError_t launch_mm(int T, int NC, int KD, int a_cols, int c_cols, const
 }
 
 hipError_t launch_prepare_matrix(int D, int L, int K, int sets, bool expanding, const int32_t *offsets,
-                                 const void *values, void *forward_operand, void *backward_operand, hipStream_t stream)
+                                 const void *values, void *forward_operand, void *backward_operand, hipStream_t stream,
+                                 const float *alpha)
 {
     // The forward product is the masked gather when the layer expands (M <= N), else the plain gather.  The sets'
     // forward operands stand side by side (every set has outputs of its own), their backward-input operands on top
@@ -782,7 +787,7 @@ hipError_t launch_prepare_matrix(int D, int L, int K, int sets, bool expanding, 
                        offsets, static_cast<const uint16_t *>(values),
                        static_cast<uint16_t *>(expanding ? forward_operand : backward_operand),
                        static_cast<uint16_t *>(expanding ? backward_operand : forward_operand),
-                       expanding ? side_by_side : stacked, expanding ? stacked : side_by_side);
+                       expanding ? side_by_side : stacked, expanding ? stacked : side_by_side, alpha);
     return hipGetLastError();
 }
 
@@ -796,7 +801,7 @@ hipError_t launch_prepare_matrix_batched(int D, int L, int K, int layers, bool e
     uint16_t *first = static_cast<uint16_t *>(prepared);
     hipLaunchKernelGGL(materialize_kernel, dim3(D + L, layers), dim3(256), size_t(D) * sizeof(float), stream, D, L, K, D,
                        offsets, static_cast<const uint16_t *>(values), expanding ? first : first + operand,
-                       expanding ? first + operand : first, masked, gather);
+                       expanding ? first + operand : first, masked, gather, static_cast<const float *>(nullptr));
     return hipGetLastError();
 }
 
@@ -871,7 +876,8 @@ hipError_t launch_product_matrix(const ProductArgs &a, hipStream_t stream)
         if (a.src_sets != 1 || a.dst_sets != 1) return hipErrorInvalidValue;  // groups come prepared
         const OperandPlace place = {KD, 0, 0, 0};
         hipLaunchKernelGGL(materialize_kernel, dim3(NC), dim3(256), size_t(KD) * sizeof(float), stream, a.D, a.L, a.K,
-                           a.masked ? NC : 0, a.offsets, static_cast<const uint16_t *>(a.values), Wf, Wf, place, place);
+                           a.masked ? NC : 0, a.offsets, static_cast<const uint16_t *>(a.values), Wf, Wf, place, place,
+                           static_cast<const float *>(nullptr));
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

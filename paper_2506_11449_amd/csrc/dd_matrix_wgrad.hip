@@ -87,10 +87,13 @@ __global__ __launch_bounds__(kWgT, kWgPerCu) void wgrad_mm_kernel(int T, int D, 
                                                                   const uint16_t *__restrict__ A,
                                                                   const uint16_t *__restrict__ B,
                                                                   const int *__restrict__ offsets,
-                                                                  float *__restrict__ partial)
+                                                                  float *__restrict__ partial,
+                                                                  unsigned *__restrict__ ticket)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     using Tl = WgTile<TP, TQ>;
+    // the reduction that follows may count its workgroups on this word; it has to start from zero
+    if (ticket && blockIdx.x == 0 && threadIdx.x == 0) *ticket = 0u;
     constexpr int kARow = Tl::ARow, kBRow = Tl::BRow, kABytes = Tl::ABytes, kStageBytes = Tl::StageBytes;
     int *table = reinterpret_cast<int *>(smem + kWgRing * kStageBytes);  // [Window]: offset -> first diagonal
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -373,10 +376,19 @@ __global__ __launch_bounds__(kWgT, kWgPerCu) void wgrad_mm_kernel(int T, int D, 
 // sums are then added in run order: a fixed order, so the result is the same on every call.
 // Repeated offsets are rare, so the first eight partial sums of diagonal k itself are requested before the search
 // for rep(k) (whose loads and barriers they then overlap) and fetched again only if k turns out not to be first.
+//
+// SCALED: the adjoint of the scaling by the importance weights (Sec. 3.2 Eq. 4) as the epilogue: the sum g = dValues[k][p]
+// leaves as alpha[o_k] * g, and <dValues[k], V[k]> is summed per workgroup into dots[k][blockIdx.x]; the workgroup
+// that finishes last (one ticket per workgroup on a word the matrix kernel has zeroed) adds, for every candidate i,
+// the dots of the diagonals with offset i: dalpha[i].  Fixed orders throughout (but for offsets repeated three times or
+// more), so still reproducible.
+template <bool SCALED>
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(int D, int L, int K, int splits,
                                                            const int *__restrict__ offsets,
                                                            const float *__restrict__ partial,
-                                                           float *__restrict__ dV)
+                                                           float *__restrict__ dV, const float *__restrict__ alpha,
+                                                           const uint16_t *__restrict__ V, float *__restrict__ dots,
+                                                           unsigned *__restrict__ ticket, float *__restrict__ dalpha)
 {
     __shared__ int rep_s;
     __shared__ f32x4 run_s[3][64];
@@ -431,9 +443,41 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(int D, int L, int K, 
     }
     if (run > 0) run_s[run - 1][g] = acc;
     __syncthreads();
-    if (run == 0 && active) {
-        acc = ((acc + run_s[0][g]) + run_s[1][g]) + run_s[2][g];
-        *reinterpret_cast<f32x4 *>(dV + size_t(k) * L + p) = acc;
+    if (run == 0 && active) acc = ((acc + run_s[0][g]) + run_s[1][g]) + run_s[2][g];
+    if (!SCALED) {
+        if (run == 0 && active) *reinterpret_cast<f32x4 *>(dV + size_t(k) * L + p) = acc;
+        return;
+    }
+    __shared__ int last_s;
+    if (run == 0) {  // exactly the first wave
+        float dot = 0.f;
+        if (active) {
+            const uint16_t *v = V + size_t(k) * L + p;
+            dot = fmaf(acc[3], bf16_to_f32(v[3]), fmaf(acc[2], bf16_to_f32(v[2]), fmaf(acc[1], bf16_to_f32(v[1]), acc[0] * bf16_to_f32(v[0]))));
+            const float a = alpha[mine];
+            const f32x4 scaled = {a * acc[0], a * acc[1], a * acc[2], a * acc[3]};
+            *reinterpret_cast<f32x4 *>(dV + size_t(k) * L + p) = scaled;
+        }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) dot += __shfl_xor(dot, d, 64);
+        if (g == 0) {
+            dots[size_t(k) * gridDim.x + blockIdx.x] = dot;
+            __threadfence();  // the dot is visible device-wide before the ticket is drawn
+            last_s = atomicAdd(ticket, 1u) == gridDim.x * gridDim.y - 1;
+        }
+    }
+    __syncthreads();
+    if (!last_s) return;
+    __threadfence();  // every other workgroup's dots are visible to all threads of this one
+    for (int i = threadIdx.x; i < D; i += 256) dalpha[i] = 0.f;
+    __threadfence();
+    __syncthreads();
+    // one addition per diagonal: candidates without a diagonal stay 0, an offset given twice gets both dots (a sum of two
+    // is the same in either order; only an offset given three or more times sees an unspecified order of fp32 adds)
+    for (int j = threadIdx.x; j < K; j += 256) {
+        float sum = 0.f;
+        for (unsigned b = 0; b < gridDim.x; ++b) sum += __builtin_nontemporal_load(dots + size_t(j) * gridDim.x + b);
+        atomicAdd(dalpha + canonical_offset(offsets[j], D), sum);
     }
 }
 
@@ -494,7 +538,8 @@ size_t weight_grad_matrix_ws_bytes(int64_t T, int D, int L, int K)
 }
 
 template <int TP, int TQ>
-static hipError_t launch_wgrad_mm(const WeightGradArgs &a, const WgradPlan &pl, float *partial, hipStream_t stream)
+static hipError_t launch_wgrad_mm(const WeightGradArgs &a, const WgradPlan &pl, float *partial, unsigned *ticket,
+                                  hipStream_t stream)
 {
     using Tl = WgTile<TP, TQ>;
     static std::atomic<uint64_t> lds_allowed{0};  // one bit per device
@@ -502,20 +547,47 @@ static hipError_t launch_wgrad_mm(const WeightGradArgs &a, const WgradPlan &pl, 
     const int lds_bytes = Tl::LdsBytes;
     hipLaunchKernelGGL((wgrad_mm_kernel<TP, TQ>), dim3(pl.grid), dim3(kWgT), lds_bytes, stream, int(a.T), a.D, a.L,
                        a.K, pl.tiles_p, pl.tiles_q, pl.splits, pl.slices, pl.skew,
-                       static_cast<const uint16_t *>(a.A), static_cast<const uint16_t *>(a.B), a.offsets, partial);
+                       static_cast<const uint16_t *>(a.A), static_cast<const uint16_t *>(a.B), a.offsets, partial, ticket);
     return hipGetLastError();
+}
+
+static hipError_t launch_wgrad_mm_any(const WeightGradArgs &a, const WgradPlan &pl, float *partial, unsigned *ticket,
+                                      hipStream_t stream)
+{
+    return pl.tp == 192   ? launch_wgrad_mm<192, 192>(a, pl, partial, ticket, stream)
+           : pl.tq == 256 ? launch_wgrad_mm<128, 256>(a, pl, partial, ticket, stream)
+                          : launch_wgrad_mm<128, 128>(a, pl, partial, ticket, stream);
 }
 
 hipError_t launch_weight_grad_matrix(const WeightGradArgs &a, hipStream_t stream)
 {
     const WgradPlan pl = plan_wgrad(a.T, a.D, a.L);
     float *partial = static_cast<float *>(a.ws);
-    hipError_t e = pl.tp == 192   ? launch_wgrad_mm<192, 192>(a, pl, partial, stream)
-                   : pl.tq == 256 ? launch_wgrad_mm<128, 256>(a, pl, partial, stream)
-                                  : launch_wgrad_mm<128, 128>(a, pl, partial, stream);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((a.L + 255) / 256, a.K), dim3(256), 0, stream, a.D, a.L, a.K,
-                       pl.splits, a.offsets, partial, a.dValues);
+    if (hipError_t e = launch_wgrad_mm_any(a, pl, partial, nullptr, stream)) return e;
+    hipLaunchKernelGGL(wgrad_reduce_kernel<false>, dim3((a.L + 255) / 256, a.K), dim3(256), 0, stream, a.D, a.L, a.K,
+                       pl.splits, a.offsets, partial, a.dValues, static_cast<const float *>(nullptr),
+                       static_cast<const uint16_t *>(nullptr), static_cast<float *>(nullptr),
+                       static_cast<unsigned *>(nullptr), static_cast<float *>(nullptr));
+    return hipGetLastError();
+}
+
+// tail: [K x ceil(L / 256)] dots, then the ticket
+size_t weight_grad_scaled_tail_bytes(int L, int K)
+{
+    return (size_t(K) * ((L + 255) / 256) * sizeof(float) + sizeof(unsigned) + 255) / 256 * 256;
+}
+
+hipError_t launch_weight_grad_matrix_scaled(const WeightGradArgs &a, const float *alpha, const void *V, float *dalpha,
+                                            void *tail, hipStream_t stream)
+{
+    const WgradPlan pl = plan_wgrad(a.T, a.D, a.L);
+    float *partial = static_cast<float *>(a.ws);
+    float *dots = static_cast<float *>(tail);
+    unsigned *ticket = reinterpret_cast<unsigned *>(dots + size_t(a.K) * ((a.L + 255) / 256));
+    if (hipError_t e = launch_wgrad_mm_any(a, pl, partial, ticket, stream)) return e;
+    hipLaunchKernelGGL(wgrad_reduce_kernel<true>, dim3((a.L + 255) / 256, a.K), dim3(256), 0, stream, a.D, a.L, a.K,
+                       pl.splits, a.offsets, partial, a.dValues, alpha, static_cast<const uint16_t *>(V), dots, ticket,
+                       dalpha);
     return hipGetLastError();
 }
 
