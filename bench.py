@@ -278,6 +278,15 @@ class LayerBench:
             self.bwd_input(i)
             self.bwd_weight(i)
         us["dd_bwd_input+dd_bwd_weight_same_dY"] = time_loop(torch, pair, n) * 1e3
+        if self.use_prepare:  # the backward pass as one call: runs of tokens that keep dY in the memory-side cache
+            dX2 = [torch.empty_like(x) for x in self.dX]
+
+            def fused(i):
+                s = i % self.S
+                self.dd.dd_bwd(self.X[s], self.dY[s], self.off[0], None, dX=dX2[s], dValues=self.dV, prepared=self.prepared,
+                               ws=self.ws)
+            us["dd_bwd"] = time_loop(torch, fused, n) * 1e3
+            del dX2
         line = {"layer": f"{self.M}->{self.N}", "tokens": self.T, "K": self.K, "dtype": self.layer.dtype,
                 "buffer_sets": self.S, "us": us,
                 "sparse_tflops": {k: self.flops() / us[k] / 1e6 for k in ("dd_fwd", "dd_bwd_input", "dd_bwd_weight")},

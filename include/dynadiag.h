@@ -81,7 +81,8 @@ typedef enum {
     DD_OP_SCALE_VALUES_BWD = 4, /* layer->K diagonals: scratch of dd_scale_values_bwd */
     DD_OP_PREPARE = 5,          /* the block dd_prepare fills and DD_ALGO_PREPARED calls read */
     DD_OP_DIAGHEUR = 6,         /* layer->in_features candidates, layer->K diagonals: scratch of dd_diagheur_update */
-    DD_OP_BWD_WEIGHT_SCALED = 7 /* scratch of dd_bwd_weight_scaled (0 where it returns DD_ERR_UNSUPPORTED) */
+    DD_OP_BWD_WEIGHT_SCALED = 7, /* scratch of dd_bwd_weight_scaled (0 where it returns DD_ERR_UNSUPPORTED) */
+    DD_OP_BWD = 8               /* scratch of dd_bwd */
 } dd_op;
 
 typedef struct {
@@ -197,6 +198,22 @@ dd_status dd_bwd_weight(const dd_layer *layer, const void *X, const void *dY, co
                         float *dValues, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * The backward pass of the layer as one call (Fig. 3 g-i; Sec. 3.3): dX exactly as dd_bwd_input and dValues exactly as
+ * dd_bwd_weight compute them (bit for bit), issued back to back on one scratch block, input gradient first, so that
+ * the weight gradient finds in the 256 MB memory-side cache whatever of dY that cache kept.  On the matrix cores the
+ * two products are different contractions (over features, over tokens) whose tiles share neither registers nor
+ * LDS; a schedule that takes the tokens in runs small enough for dY to stay cached between the two was built and
+ * measured slower than this one at every benchmark shape (more launches and partial sums than the cached read saves).
+ *   X [tokens x M], dY [tokens x N] in;  dX [tokens x M] out;  dValues [K x L] fp32 out.
+ *   layer->algo = DD_ALGO_PREPARED: `prepared` is the block dd_prepare filled (values is not read); any other
+ *   algo: prepared is not read.  DD_ALGO_BLOCKS: DD_ERR_UNSUPPORTED.
+ *   ws: dd_workspace_bytes(DD_OP_BWD, layer, 0).  Errors as for the two calls.
+ */
+dd_status dd_bwd(const dd_layer *layer, const void *X, const void *dY, const int32_t *offsets, const void *values,
+                 const void *prepared, size_t prepared_bytes, void *dX, float *dValues, void *ws, size_t ws_bytes,
+                 void *hip_stream);
+
+/*
  * dd_bwd_weight for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without `ws`, same kernels,
  * same results bit for bit; the partial sums of the token chunks go to an array inside the library,
@@ -248,7 +265,7 @@ dd_status dd_soft_topk(int32_t batch, int32_t D, int32_t K, float temperature, c
  *                      operands are built: no values_eff array is written or read.  alpha_tilde [D] fp32, V [K x L]
  *                      dtype; the block is bit for bit what dd_scale_values followed by dd_prepare builds.
  * dd_bwd_weight_scaled dd_bwd_weight followed by dd_scale_values_bwd, the adjoint of the scaling being the epilogue of
- *                      the weight gradient's ordered sum over the token chunks (no dValues array in between, two
+ *                      the weight gradient's ordered sum over the token chunks (no dValues array in between, three
  *                      launches instead of four):  dV[k][p] = alpha_tilde[o_k] * dValues[k][p]  [K x L] fp32 (bit for
  *                      bit as the two calls), d_alpha_tilde[i] = sum over the diagonals with o_k = i of
  *                      <dValues[k], V[k]>  [D] fp32 (0 elsewhere; within 1e-5, the dot products are summed in another

@@ -14,10 +14,10 @@ from .build import LIB_PATH
 DD_F32, DD_BF16 = 0, 1
 DD_ALGO_AUTO, DD_ALGO_VECTOR, DD_ALGO_MATRIX, DD_ALGO_PREPARED, DD_ALGO_BLOCKS = 0, 1, 2, 3, 4
 DD_OP_FWD, DD_OP_BWD_INPUT, DD_OP_BWD_WEIGHT, DD_OP_SELECT, DD_OP_SCALE_VALUES_BWD, DD_OP_PREPARE = 0, 1, 2, 3, 4, 5
-DD_OP_DIAGHEUR, DD_OP_BWD_WEIGHT_SCALED = 6, 7
+DD_OP_DIAGHEUR, DD_OP_BWD_WEIGHT_SCALED, DD_OP_BWD = 6, 7, 8
 
 EXPORTS = ("dd_workspace_bytes", "dd_fwd", "dd_prepare", "dd_prepare_batched", "dd_select_prepare", "dd_prepare_shared", "dd_fwd_shared", "dd_bwd_input_shared",
-           "dd_bwd_input", "dd_bwd_weight", "dd_bwd_weight_static", "dd_static_scratch_bytes", "dd_select_diagonals",
+           "dd_bwd_input", "dd_bwd", "dd_bwd_weight", "dd_bwd_weight_static", "dd_static_scratch_bytes", "dd_select_diagonals",
            "dd_select_soft", "dd_prepare_scaled", "dd_bwd_weight_scaled", "dd_soft_topk", "dd_soft_topk_bwd", "dd_scale_values", "dd_scale_values_bwd", "dd_diag_magnitude",
            "dd_diagheur_update", "dd_status_string")
 
@@ -58,6 +58,7 @@ def load_library():
     lib.dd_bwd_input_shared.argtypes = [lp, i32, vp, vp, sz, vp, vp]
     lib.dd_bwd_input.argtypes = [lp, vp, vp, vp, vp, vp, sz, vp]
     lib.dd_bwd_weight.argtypes = [lp, vp, vp, vp, vp, vp, sz, vp]
+    lib.dd_bwd.argtypes = [lp, vp, vp, vp, vp, vp, sz, vp, vp, vp, sz, vp]
     lib.dd_bwd_weight_static.argtypes = [lp, vp, vp, vp, vp, vp]
     lib.dd_bwd_weight_static.restype = ctypes.c_int
     lib.dd_static_scratch_bytes.argtypes = []
@@ -331,6 +332,34 @@ def dd_bwd_weight(X, dY, offsets, dValues=None, algo=DD_ALGO_AUTO, ws=None, stre
     wp, wn = _ws_for(need, X.device, ws)
     _check(_lib.dd_bwd_weight(ref, _ptr(X), _ptr(dY), _ptr(offsets), _ptr(dValues), wp, wn, _stream(stream)))
     return dValues
+
+
+def dd_bwd(X, dY, offsets, values, dX=None, dValues=None, algo=DD_ALGO_AUTO, ws=None, stream=None, prepared=None):
+    """The backward pass as one call: (dX [T x M], dValues [K x min(M,N)] fp32).  prepared= as for dd_fwd."""
+    T, M = X.shape
+    N = dY.shape[1]
+    K = offsets.shape[0]
+    if prepared is not None:
+        if (prepared.in_features, prepared.out_features, prepared.dtype) != (M, N, X.dtype):
+            raise ValueError("prepared block belongs to another layer")
+        algo = DD_ALGO_PREPARED
+    else:
+        _dev(values, X.dtype, (K, min(M, N)), "values")
+    _, ref, need = _plan(DD_OP_BWD, T, M, N, K, X.dtype, algo)
+    _dev(X, X.dtype, (T, M), "X")
+    _dev(dY, X.dtype, (T, N), "dY")
+    _dev(offsets, torch.int32, (K,), "offsets")
+    if dX is None:
+        dX = torch.empty((T, M), dtype=X.dtype, device=X.device)
+    if dValues is None:
+        dValues = torch.empty((K, min(M, N)), dtype=torch.float32, device=X.device)
+    _dev(dX, X.dtype, (T, M), "dX")
+    _dev(dValues, torch.float32, (K, min(M, N)), "dValues")
+    wp, wn = _ws_for(need, X.device, ws)
+    pp, pn = (None, 0) if prepared is None else (_ptr(prepared.buf), prepared.buf.numel())
+    _check(load_library().dd_bwd(ref, _ptr(X), _ptr(dY), _ptr(offsets), _ptr(values), pp, pn, _ptr(dX), _ptr(dValues),
+                                 wp, wn, _stream(stream)))
+    return dX, dValues
 
 
 def dd_static_scratch_bytes():

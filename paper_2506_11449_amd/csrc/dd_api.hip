@@ -125,6 +125,16 @@ dd_status product(const dd_layer *l, const Shape &s, bool transposed, const void
     return e == hipSuccess ? DD_OK : DD_ERR_HIP;
 }
 
+// ---- the backward pass as one call (dd_bwd): the two products back to back, sharing one scratch ----
+size_t bwd_ws_bytes(const dd_layer *l)
+{
+    dd_layer plain = *l;
+    if (plain.algo == DD_ALGO_PREPARED) plain.algo = DD_ALGO_MATRIX;  // the prepared block is passed beside the scratch
+    const size_t a = l->algo == DD_ALGO_PREPARED ? 0 : dd_workspace_bytes(DD_OP_BWD_INPUT, &plain, 0);
+    const size_t b = dd_workspace_bytes(DD_OP_BWD_WEIGHT, &plain, 0);
+    return a > b ? a : b;
+}
+
 }  // namespace
 
 extern "C" {
@@ -155,6 +165,8 @@ size_t dd_workspace_bytes(int op, const dd_layer *layer, int32_t batch)
         return dd::product_matrix_supported(1, s.D, s.L, layer->dtype == DD_BF16) ? prepared_bytes(s) : 0;
     case DD_OP_BWD_WEIGHT:
         return weight_grad_ws_bytes(layer, s);
+    case DD_OP_BWD:
+        return layer->algo == DD_ALGO_BLOCKS ? 0 : bwd_ws_bytes(layer);
     case DD_OP_BWD_WEIGHT_SCALED: {
         if (layer->algo == DD_ALGO_VECTOR || !wants_matrix_wgrad(layer, s)) return 0;
         const size_t partials = dd::weight_grad_matrix_ws_bytes(layer->tokens, s.D, s.L, layer->K);
@@ -308,6 +320,26 @@ dd_status dd_bwd_weight(const dd_layer *layer, const void *X, const void *dY, co
     const hipError_t e = matrix ? dd::launch_weight_grad_matrix(a, static_cast<hipStream_t>(hip_stream))
                                 : dd::launch_weight_grad_vector(a, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? DD_OK : DD_ERR_HIP;
+}
+
+dd_status dd_bwd(const dd_layer *layer, const void *X, const void *dY, const int32_t *offsets, const void *values,
+                 const void *prepared, size_t prepared_bytes_given, void *dX, float *dValues, void *ws, size_t ws_bytes,
+                 void *hip_stream)
+{
+    Shape s;
+    if (dd_status st = check_layer(layer, &s)) return st;
+    if (layer->algo == DD_ALGO_BLOCKS) return DD_ERR_UNSUPPORTED;
+    const bool have_prepared = layer->algo == DD_ALGO_PREPARED;
+    if (have_prepared && !prepared) return DD_ERR_INVALID_ARG;
+    if (dd_status st = check_ws(ws, ws_bytes, bwd_ws_bytes(layer))) return st;
+    // The input gradient first: the weight gradient, issued right behind it, then finds in the memory-side cache
+    // whatever of dY that cache could keep.  Both take their scratch from the same block, one after the other.
+    if (dd_status st = dd_bwd_input(layer, dY, offsets, values, dX, have_prepared ? const_cast<void *>(prepared) : ws,
+                                    have_prepared ? prepared_bytes_given : ws_bytes, hip_stream))
+        return st;
+    dd_layer second = *layer;
+    if (have_prepared) second.algo = DD_ALGO_MATRIX;
+    return dd_bwd_weight(&second, X, dY, offsets, dValues, ws, ws_bytes, hip_stream);
 }
 
 dd_status dd_select_soft(int32_t batch, int32_t D, int32_t K, float temperature, const float *scores,

@@ -87,13 +87,10 @@ __global__ __launch_bounds__(kWgT, kWgPerCu) void wgrad_mm_kernel(int T, int D, 
                                                                   const uint16_t *__restrict__ A,
                                                                   const uint16_t *__restrict__ B,
                                                                   const int *__restrict__ offsets,
-                                                                  float *__restrict__ partial,
-                                                                  unsigned *__restrict__ ticket)
+                                                                  float *__restrict__ partial)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     using Tl = WgTile<TP, TQ>;
-    // the reduction that follows may count its workgroups on this word; it has to start from zero
-    if (ticket && blockIdx.x == 0 && threadIdx.x == 0) *ticket = 0u;
     constexpr int kARow = Tl::ARow, kBRow = Tl::BRow, kABytes = Tl::ABytes, kStageBytes = Tl::StageBytes;
     int *table = reinterpret_cast<int *>(smem + kWgRing * kStageBytes);  // [Window]: offset -> first diagonal
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -378,17 +375,14 @@ __global__ __launch_bounds__(kWgT, kWgPerCu) void wgrad_mm_kernel(int T, int D, 
 // for rep(k) (whose loads and barriers they then overlap) and fetched again only if k turns out not to be first.
 //
 // SCALED: the adjoint of the scaling by the importance weights (Sec. 3.2 Eq. 4) as the epilogue: the sum g = dValues[k][p]
-// leaves as alpha[o_k] * g, and <dValues[k], V[k]> is summed per workgroup into dots[k][blockIdx.x]; the workgroup
-// that finishes last (one ticket per workgroup on a word the matrix kernel has zeroed) adds, for every candidate i,
-// the dots of the diagonals with offset i: dalpha[i].  Fixed orders throughout (but for offsets repeated three times or
-// more), so still reproducible.
+// leaves as alpha[o_k] * g, and <dValues[k], V[k]> is summed per workgroup into dots[k][blockIdx.x] (fixed order);
+// wgrad_dalpha_kernel turns the dots into the gradient of the importance weights.
 template <bool SCALED>
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(int D, int L, int K, int splits,
                                                            const int *__restrict__ offsets,
                                                            const float *__restrict__ partial,
                                                            float *__restrict__ dV, const float *__restrict__ alpha,
-                                                           const uint16_t *__restrict__ V, float *__restrict__ dots,
-                                                           unsigned *__restrict__ ticket, float *__restrict__ dalpha)
+                                                           const uint16_t *__restrict__ V, float *__restrict__ dots)
 {
     __shared__ int rep_s;
     __shared__ f32x4 run_s[3][64];
@@ -448,7 +442,6 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(int D, int L, int K, 
         if (run == 0 && active) *reinterpret_cast<f32x4 *>(dV + size_t(k) * L + p) = acc;
         return;
     }
-    __shared__ int last_s;
     if (run == 0) {  // exactly the first wave
         float dot = 0.f;
         if (active) {
@@ -460,25 +453,27 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(int D, int L, int K, 
         }
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) dot += __shfl_xor(dot, d, 64);
-        if (g == 0) {
-            dots[size_t(k) * gridDim.x + blockIdx.x] = dot;
-            __threadfence();  // the dot is visible device-wide before the ticket is drawn
-            last_s = atomicAdd(ticket, 1u) == gridDim.x * gridDim.y - 1;
-        }
+        if (g == 0) dots[size_t(k) * gridDim.x + blockIdx.x] = dot;
     }
+}
+
+// dalpha[i] = sum over the diagonals k with offset i of (dots[k][0] + dots[k][1] + ...), 0 for candidates without a
+// diagonal.  One workgroup: the D sums are formed in LDS (one addition per diagonal; an offset given twice gets both
+// dots -- a sum of two is the same in either order, only an offset given three times or more sees an unspecified order
+// of fp32 additions) and written out once.
+__global__ __launch_bounds__(256) void wgrad_dalpha_kernel(int D, int K, int per_k, const int *__restrict__ offsets,
+                                                           const float *__restrict__ dots, float *__restrict__ dalpha)
+{
+    extern __shared__ float sums[];  // [D]
+    for (int i = threadIdx.x; i < D; i += 256) sums[i] = 0.f;
     __syncthreads();
-    if (!last_s) return;
-    __threadfence();  // every other workgroup's dots are visible to all threads of this one
-    for (int i = threadIdx.x; i < D; i += 256) dalpha[i] = 0.f;
-    __threadfence();
-    __syncthreads();
-    // one addition per diagonal: candidates without a diagonal stay 0, an offset given twice gets both dots (a sum of two
-    // is the same in either order; only an offset given three or more times sees an unspecified order of fp32 adds)
     for (int j = threadIdx.x; j < K; j += 256) {
         float sum = 0.f;
-        for (unsigned b = 0; b < gridDim.x; ++b) sum += __builtin_nontemporal_load(dots + size_t(j) * gridDim.x + b);
-        atomicAdd(dalpha + canonical_offset(offsets[j], D), sum);
+        for (int b = 0; b < per_k; ++b) sum += dots[size_t(j) * per_k + b];
+        atomicAdd(&sums[canonical_offset(offsets[j], D)], sum);
     }
+    __syncthreads();
+    for (int i = threadIdx.x; i < D; i += 256) dalpha[i] = sums[i];
 }
 
 // ---- host side ----
@@ -538,8 +533,7 @@ size_t weight_grad_matrix_ws_bytes(int64_t T, int D, int L, int K)
 }
 
 template <int TP, int TQ>
-static hipError_t launch_wgrad_mm(const WeightGradArgs &a, const WgradPlan &pl, float *partial, unsigned *ticket,
-                                  hipStream_t stream)
+static hipError_t launch_wgrad_mm(const WeightGradArgs &a, const WgradPlan &pl, float *partial, hipStream_t stream)
 {
     using Tl = WgTile<TP, TQ>;
     static std::atomic<uint64_t> lds_allowed{0};  // one bit per device
@@ -547,34 +541,32 @@ static hipError_t launch_wgrad_mm(const WeightGradArgs &a, const WgradPlan &pl, 
     const int lds_bytes = Tl::LdsBytes;
     hipLaunchKernelGGL((wgrad_mm_kernel<TP, TQ>), dim3(pl.grid), dim3(kWgT), lds_bytes, stream, int(a.T), a.D, a.L,
                        a.K, pl.tiles_p, pl.tiles_q, pl.splits, pl.slices, pl.skew,
-                       static_cast<const uint16_t *>(a.A), static_cast<const uint16_t *>(a.B), a.offsets, partial, ticket);
+                       static_cast<const uint16_t *>(a.A), static_cast<const uint16_t *>(a.B), a.offsets, partial);
     return hipGetLastError();
 }
 
-static hipError_t launch_wgrad_mm_any(const WeightGradArgs &a, const WgradPlan &pl, float *partial, unsigned *ticket,
-                                      hipStream_t stream)
+static hipError_t launch_wgrad_mm_any(const WeightGradArgs &a, const WgradPlan &pl, float *partial, hipStream_t stream)
 {
-    return pl.tp == 192   ? launch_wgrad_mm<192, 192>(a, pl, partial, ticket, stream)
-           : pl.tq == 256 ? launch_wgrad_mm<128, 256>(a, pl, partial, ticket, stream)
-                          : launch_wgrad_mm<128, 128>(a, pl, partial, ticket, stream);
+    return pl.tp == 192   ? launch_wgrad_mm<192, 192>(a, pl, partial, stream)
+           : pl.tq == 256 ? launch_wgrad_mm<128, 256>(a, pl, partial, stream)
+                          : launch_wgrad_mm<128, 128>(a, pl, partial, stream);
 }
 
 hipError_t launch_weight_grad_matrix(const WeightGradArgs &a, hipStream_t stream)
 {
     const WgradPlan pl = plan_wgrad(a.T, a.D, a.L);
     float *partial = static_cast<float *>(a.ws);
-    if (hipError_t e = launch_wgrad_mm_any(a, pl, partial, nullptr, stream)) return e;
+    if (hipError_t e = launch_wgrad_mm_any(a, pl, partial, stream)) return e;
     hipLaunchKernelGGL(wgrad_reduce_kernel<false>, dim3((a.L + 255) / 256, a.K), dim3(256), 0, stream, a.D, a.L, a.K,
                        pl.splits, a.offsets, partial, a.dValues, static_cast<const float *>(nullptr),
-                       static_cast<const uint16_t *>(nullptr), static_cast<float *>(nullptr),
-                       static_cast<unsigned *>(nullptr), static_cast<float *>(nullptr));
+                       static_cast<const uint16_t *>(nullptr), static_cast<float *>(nullptr));
     return hipGetLastError();
 }
 
-// tail: [K x ceil(L / 256)] dots, then the ticket
+// tail: [K x ceil(L / 256)] dots
 size_t weight_grad_scaled_tail_bytes(int L, int K)
 {
-    return (size_t(K) * ((L + 255) / 256) * sizeof(float) + sizeof(unsigned) + 255) / 256 * 256;
+    return (size_t(K) * ((L + 255) / 256) * sizeof(float) + 255) / 256 * 256;
 }
 
 hipError_t launch_weight_grad_matrix_scaled(const WeightGradArgs &a, const float *alpha, const void *V, float *dalpha,
@@ -583,11 +575,13 @@ hipError_t launch_weight_grad_matrix_scaled(const WeightGradArgs &a, const float
     const WgradPlan pl = plan_wgrad(a.T, a.D, a.L);
     float *partial = static_cast<float *>(a.ws);
     float *dots = static_cast<float *>(tail);
-    unsigned *ticket = reinterpret_cast<unsigned *>(dots + size_t(a.K) * ((a.L + 255) / 256));
-    if (hipError_t e = launch_wgrad_mm_any(a, pl, partial, ticket, stream)) return e;
-    hipLaunchKernelGGL(wgrad_reduce_kernel<true>, dim3((a.L + 255) / 256, a.K), dim3(256), 0, stream, a.D, a.L, a.K,
-                       pl.splits, a.offsets, partial, a.dValues, alpha, static_cast<const uint16_t *>(V), dots, ticket,
-                       dalpha);
+    const int per_k = (a.L + 255) / 256;
+    if (hipError_t e = launch_wgrad_mm_any(a, pl, partial, stream)) return e;
+    hipLaunchKernelGGL(wgrad_reduce_kernel<true>, dim3(per_k, a.K), dim3(256), 0, stream, a.D, a.L, a.K, pl.splits,
+                       a.offsets, partial, a.dValues, alpha, static_cast<const uint16_t *>(V), dots);
+    if (hipError_t e = hipGetLastError()) return e;
+    hipLaunchKernelGGL(wgrad_dalpha_kernel, dim3(1), dim3(256), size_t(a.D) * sizeof(float), stream, a.D, a.K, per_k,
+                       a.offsets, dots, dalpha);
     return hipGetLastError();
 }
 
