@@ -205,3 +205,106 @@ def test_weight_gradient_workspace_covers_whichever_family_runs(lib):
             sizes[algo] = lib.dd_workspace_bytes(binding.DD_OP_BWD_WEIGHT, ctypes.byref(l), 0)
         assert sizes[binding.DD_ALGO_AUTO] == max(sizes[binding.DD_ALGO_VECTOR], sizes[binding.DD_ALGO_MATRIX])
         assert sizes[binding.DD_ALGO_PREPARED] == sizes[binding.DD_ALGO_MATRIX] > 0
+
+
+def test_batched_prepare_rules(lib):
+    one, blk = ctypes.c_void_p(256), ctypes.c_void_p(512)
+    ok = _layer(T=0, M=768, N=3072, K=30, dtype=1)
+    per = lib.dd_workspace_bytes(binding.DD_OP_PREPARE, ctypes.byref(ok), 0)
+    assert per % 256 == 0  # layer i's block starts where layer i-1's ends, and must be as aligned as a block of its own
+    assert lib.dd_prepare_batched(ctypes.byref(ok), -1, one, one, blk, 12 * per, None) == 1
+    assert lib.dd_prepare_batched(ctypes.byref(ok), 0, None, None, None, 0, None) == 0   # nothing to do
+    assert lib.dd_prepare_batched(ctypes.byref(ok), 12, None, one, blk, 12 * per, None) == 1
+    assert lib.dd_prepare_batched(ctypes.byref(ok), 12, one, None, blk, 12 * per, None) == 1
+    assert lib.dd_prepare_batched(ctypes.byref(ok), 12, one, one, blk, 12 * per - 1, None) == 3
+    assert lib.dd_prepare_batched(ctypes.byref(ok), 12, one, one, None, 12 * per, None) == 3
+    assert lib.dd_prepare_batched(ctypes.byref(ok), 70000, one, one, blk, 1 << 62, None) == 2
+    for bad in (_layer(M=768, N=768, K=8, dtype=0), _layer(M=100, N=768, K=8, dtype=1),
+                _layer(M=768, N=768, K=8, dtype=1, algo=binding.DD_ALGO_VECTOR)):
+        assert lib.dd_prepare_batched(ctypes.byref(bad), 3, one, one, blk, 1 << 30, None) == 2
+
+
+def test_soft_path_folded_rules(lib):
+    one, blk = ctypes.c_void_p(256), ctypes.c_void_p(512)
+    f = ctypes.c_float
+    assert lib.dd_select_soft(1, 8, 0, f(1.0), one, one, one, None) == 1
+    assert lib.dd_select_soft(1, 8, 9, f(1.0), one, one, one, None) == 1
+    assert lib.dd_select_soft(1, 8, 2, f(0.0), one, one, one, None) == 1      # temperature must be positive
+    assert lib.dd_select_soft(1, 8, 2, f(float("nan")), one, one, one, None) == 1
+    assert lib.dd_select_soft(1, 8, 2, f(1.0), None, one, one, None) == 1
+    assert lib.dd_select_soft(1, 8, 2, f(1.0), one, None, one, None) == 1
+    assert lib.dd_select_soft(1, 8, 2, f(1.0), one, one, None, None) == 1
+    assert lib.dd_select_soft(1, 1 << 20, 2, f(1.0), one, one, one, None) == 2
+    assert lib.dd_select_soft(0, 8, 2, f(1.0), None, None, None, None) == 0
+    ok = _layer(T=100, M=768, N=768, K=30, dtype=1)
+    need = lib.dd_workspace_bytes(binding.DD_OP_PREPARE, ctypes.byref(ok), 0)
+    assert lib.dd_prepare_scaled(ctypes.byref(ok), None, one, one, blk, need, None) == 1
+    assert lib.dd_prepare_scaled(ctypes.byref(ok), one, None, one, blk, need, None) == 1
+    assert lib.dd_prepare_scaled(ctypes.byref(ok), one, one, None, blk, need, None) == 1
+    assert lib.dd_prepare_scaled(ctypes.byref(ok), one, one, one, blk, need - 1, None) == 3
+    assert lib.dd_prepare_scaled(ctypes.byref(_layer(M=768, N=768, K=8, dtype=0)), one, one, one, blk, need, None) == 2
+    ws_need = lib.dd_workspace_bytes(binding.DD_OP_BWD_WEIGHT_SCALED, ctypes.byref(ok), 0)
+    plain = lib.dd_workspace_bytes(binding.DD_OP_BWD_WEIGHT, ctypes.byref(_layer(T=100, M=768, N=768, K=30, dtype=1, algo=binding.DD_ALGO_MATRIX)), 0)
+    assert ws_need > plain > 0  # the partial sums, then the dot products
+    args = lambda **kw: [kw.get(k, one) for k in ("X", "dY", "off", "alpha", "V", "dV", "dalpha")]
+    for missing in ("X", "dY", "off", "alpha", "V", "dV", "dalpha"):
+        assert lib.dd_bwd_weight_scaled(ctypes.byref(ok), *args(**{missing: None}), blk, ws_need, None) == 1
+    assert lib.dd_bwd_weight_scaled(ctypes.byref(ok), *args(), blk, ws_need - 1, None) == 3
+    assert lib.dd_bwd_weight_scaled(ctypes.byref(ok), *args(), None, ws_need, None) == 3
+    for bad in (_layer(T=8, M=768, N=768, K=8, dtype=0), _layer(T=8, M=100, N=768, K=8, dtype=1),
+                _layer(T=8, M=768, N=768, K=8, dtype=1, algo=binding.DD_ALGO_VECTOR)):
+        assert lib.dd_workspace_bytes(binding.DD_OP_BWD_WEIGHT_SCALED, ctypes.byref(bad), 0) == 0
+        assert lib.dd_bwd_weight_scaled(ctypes.byref(bad), *args(), blk, 1 << 30, None) == 2
+    assert lib.dd_bwd_weight_scaled(ctypes.byref(_layer(T=0, M=768, N=768, K=8, dtype=1)), *args(), blk, 1 << 30, None) == 1
+    # X that starts at an odd element: the matrix-core kernels need 16-byte alignment
+    assert lib.dd_bwd_weight_scaled(ctypes.byref(ok), *args(X=ctypes.c_void_p(258)), blk, ws_need, None) == 2
+
+
+def test_backward_as_one_call_rules(lib):
+    one, blk = ctypes.c_void_p(256), ctypes.c_void_p(512)
+    ok = _layer(T=100, M=768, N=3072, K=30, dtype=1)
+    need = lib.dd_workspace_bytes(binding.DD_OP_BWD, ctypes.byref(ok), 0)
+    a = lib.dd_workspace_bytes(binding.DD_OP_BWD_INPUT, ctypes.byref(ok), 0)
+    b = lib.dd_workspace_bytes(binding.DD_OP_BWD_WEIGHT, ctypes.byref(ok), 0)
+    assert need == max(a, b)  # the two products take their scratch from one block, one after the other
+    prep = _layer(T=100, M=768, N=3072, K=30, dtype=1, algo=binding.DD_ALGO_PREPARED)
+    forced = _layer(T=100, M=768, N=3072, K=30, dtype=1, algo=binding.DD_ALGO_MATRIX)
+    assert lib.dd_workspace_bytes(binding.DD_OP_BWD, ctypes.byref(prep), 0) == lib.dd_workspace_bytes(
+        binding.DD_OP_BWD_WEIGHT, ctypes.byref(forced), 0)
+    pb = lib.dd_workspace_bytes(binding.DD_OP_PREPARE, ctypes.byref(prep), 0)
+    # (layer, X, dY, offsets, values, prepared, prepared_bytes, dX, dValues, ws, ws_bytes, stream)
+    assert lib.dd_bwd(ctypes.byref(ok), one, one, one, one, None, 0, one, one, blk, need - 1, None) == 3
+    assert lib.dd_bwd(ctypes.byref(ok), one, one, one, one, None, 0, one, one, None, need, None) == 3
+    assert lib.dd_bwd(ctypes.byref(ok), one, one, None, one, None, 0, one, one, blk, need, None) == 1
+    assert lib.dd_bwd(ctypes.byref(ok), one, one, one, None, None, 0, one, one, blk, need, None) == 1
+    assert lib.dd_bwd(ctypes.byref(ok), one, None, one, one, None, 0, one, one, blk, need, None) == 1
+    assert lib.dd_bwd(ctypes.byref(ok), one, one, one, one, None, 0, None, one, blk, need, None) == 1
+    assert lib.dd_bwd(ctypes.byref(prep), one, one, one, None, None, pb, one, one, blk, need, None) == 1   # no block
+    assert lib.dd_bwd(ctypes.byref(prep), one, one, one, None, blk, pb - 1, one, one, blk, need, None) == 3
+    blocks = _layer(T=100, M=768, N=3072, K=30, dtype=1, algo=binding.DD_ALGO_BLOCKS)
+    assert lib.dd_workspace_bytes(binding.DD_OP_BWD, ctypes.byref(blocks), 0) == 0
+    assert lib.dd_bwd(ctypes.byref(blocks), one, one, one, one, blk, pb, one, one, blk, need, None) == 2
+
+
+def test_block_skipping_rules(lib):
+    one, blk = ctypes.c_void_p(256), ctypes.c_void_p(512)
+    l = _layer(T=64, M=768, N=768, K=77, dtype=1, algo=binding.DD_ALGO_BLOCKS)
+    need = lib.dd_workspace_bytes(binding.DD_OP_FWD, ctypes.byref(l), 0)
+    assert need == 2 * 768 * 768 * 2 == lib.dd_workspace_bytes(binding.DD_OP_BWD_INPUT, ctypes.byref(l), 0)
+    for fn in (lib.dd_fwd, lib.dd_bwd_input):
+        assert fn(ctypes.byref(l), one, None, None, one, blk, need, None) == 1       # the offsets are read
+        assert fn(ctypes.byref(l), one, one, None, one, blk, need - 1, None) == 3
+        assert fn(ctypes.byref(l), one, one, None, one, None, need, None) == 3
+        assert fn(ctypes.byref(_layer(T=64, M=768, N=768, K=77, dtype=0, algo=binding.DD_ALGO_BLOCKS)), one, one, None, one, blk, need, None) == 2
+        assert fn(ctypes.byref(_layer(T=64, M=100, N=768, K=7, dtype=1, algo=binding.DD_ALGO_BLOCKS)), one, one, None, one, blk, 1 << 30, None) == 2
+        assert fn(ctypes.byref(_layer(T=64, M=16384, N=128, K=7, dtype=1, algo=binding.DD_ALGO_BLOCKS)), one, one, None, one, blk, 1 << 30, None) == 2
+        assert fn(ctypes.byref(_layer(T=0, M=768, N=768, K=77, dtype=1, algo=binding.DD_ALGO_BLOCKS)), None, one, None, None, blk, need, None) == 0
+
+
+def test_static_scratch_rules(lib):
+    one = ctypes.c_void_p(256)
+    assert lib.dd_static_scratch_bytes() == 32 << 20
+    big = _layer(T=25216, M=1024, N=4096, K=819, dtype=1)
+    assert lib.dd_workspace_bytes(binding.DD_OP_BWD_WEIGHT, ctypes.byref(big), 0) > 32 << 20
+    assert lib.dd_bwd_weight_static(ctypes.byref(big), one, one, one, one, None) == 3      # before any launch or lookup
+    assert lib.dd_bwd_weight_static(ctypes.byref(_layer(K=0)), one, one, one, one, None) == 1
