@@ -63,7 +63,7 @@ def parse():
                     help="search hipBLASLt / rocBLAS for the fastest solution of every dense GEMM the benchmark "
                          "compares with and write them to bench_dense_gemm_tuned.csv (minutes)")
     ap.add_argument("--table", action="store_true", help="print the per-layer table as markdown instead of JSON")
-    ap.add_argument("--k-sweep", action="store_true", help="vector against matrix family over K on 768^2 and 1024^2")
+    ap.add_argument("--k-sweep", action="store_true", help="vector family, matrix family and DD_ALGO_AUTO over K on four shapes")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (a known-size reference for the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -631,18 +631,22 @@ def tune_dense(torch, dd, synth, dense):
 
 
 def k_sweep(torch, dd, synth):
-    """us per forward product, vector against matrix family (self-contained calls, as DD_ALGO_AUTO would run them)."""
+    """us per self-contained call over K: DD_ALGO_VECTOR (K <= 16: the kernels for a handful of diagonals), DD_ALGO_MATRIX
+    (dense operand rebuilt inside the call) and what DD_ALGO_AUTO picks."""
     rows = []
-    for (D, T) in ((768, 12608), (1024, 25216)):
+    for (M, N, T) in ((768, 768, 12608), (1024, 1024, 25216), (768, 3072, 25216), (3072, 768, 25216)):
+        D = max(M, N)
         for K in (1, 2, 4, 8, 12, 16, 21, 24, 32, 48, 64, D // 8):
-            l = synth.Layer(f"sweep_{D}_{K}", T, D, D, K, "bf16")
+            l = synth.Layer(f"sweep_{M}_{N}_{K}", T, M, N, K, "bf16")
             t = {}
-            for algo in ("vector", "matrix"):
+            for algo in ("vector", "matrix", "auto"):
                 b = LayerBench(torch, dd, synth, l, algo, 0, 0)
                 t[algo] = {"fwd": time_loop(torch, b.fwd_alone, 20) * 1e3,
+                           "bwd_input": time_loop(torch, b.bwd_input_alone, 20) * 1e3,
                            "bwd_weight": time_loop(torch, b.bwd_weight, 20) * 1e3}
                 del b
-            rows.append({"D": D, "T": T, "K": K, "us": t})
+            rows.append({"M": M, "N": N, "T": T, "K": K, "us": t,
+                         "hbm_floor_us": 2 * T * (M + N) / 8e12 * 1e6})
             print(json.dumps(rows[-1]), file=sys.stderr, flush=True)
     return rows
 

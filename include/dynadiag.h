@@ -31,9 +31,11 @@
  *     products: max(M, N) > 65535, or DD_ALGO_MATRIX / DD_ALGO_PREPARED forced where the matrix-core
  *     kernels do not apply.  They cover bf16 storage, 16-byte aligned matrices and M, N both multiples
  *     of 128 (dd_bwd_weight: both multiples of 192, or both of 128), max(M, N) <= 8192; DD_ALGO_AUTO
- *     takes them there at every density (they are faster than the vector kernels from K = 1 on) and the vector
- *     kernels everywhere else -- also for a matrix
- *     that is not 16-byte aligned (a view that starts at an odd element): such a call is legal under DD_ALGO_AUTO
+ *     takes them there at every density but the extreme one -- for a handful of diagonals (K <= 16 and, for a
+ *     product whose output is W columns wide, K * W <= D * L / 96; for dd_bwd_weight K <= D / 192; Sec. 4.4's
+ *     regime of >= 99 % sparsity) it takes vector kernels built for that case, whose time follows K down to
+ *     the cost of reading the input and writing the output once -- and the vector kernels everywhere else,
+ *     also for a matrix that is not 16-byte aligned (a view that starts at an odd element): such a call is legal under DD_ALGO_AUTO
  *     and several times slower; DD_ALGO_MATRIX / DD_ALGO_PREPARED report it as DD_ERR_UNSUPPORTED instead.
  *     DD_ERR_HIP: the launch itself failed.
  *   - tokens == 0 is legal: fwd / bwd_input return DD_OK without a launch; bwd_weight
@@ -63,7 +65,8 @@ typedef enum { DD_F32 = 0, DD_BF16 = 1 } dd_dtype;
 /* Which kernel family runs the product.  DD_ALGO_AUTO picks by shape and density. */
 typedef enum {
     DD_ALGO_AUTO = 0,
-    DD_ALGO_VECTOR = 1, /* direct diagonal kernels on the vector ALUs: work ~ tokens*K*L   */
+    DD_ALGO_VECTOR = 1, /* direct diagonal kernels on the vector ALUs: work ~ tokens*K*L (K <= 16, bf16, M and N
+                           multiples of 128: the kernels built for a handful of diagonals) */
     DD_ALGO_MATRIX = 2, /* the diagonals rebuilt as a dense operand in scratch, product on the matrix cores */
     DD_ALGO_PREPARED = 3, /* as DD_ALGO_MATRIX, with the dense operands already built by dd_prepare */
     DD_ALGO_BLOCKS = 4    /* as DD_ALGO_PREPARED, and the product skips every 32 x 16 block of the operand that no

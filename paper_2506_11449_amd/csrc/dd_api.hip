@@ -47,17 +47,34 @@ size_t select_ws_bytes(int32_t, int32_t, int32_t) { return 0; }
 
 bool aligned16(const void *p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
 
-// Does the shape allow the matrix-core kernels?  Then every request but DD_ALGO_VECTOR runs them.  The dense
-// contraction costs the same whatever K is and the vector kernels cost in proportion to K, but measured over K = 1 ...
-// D/8 (`bench.py --k-sweep`; 768^2 at 12608 tokens: 23.6 us against 55.8 us at K = 1, 24.3 against 123 at K = 96;
-// 1024^2 at 25216 tokens: 66 against 229 at K = 1) the matrix cores win at every density, because the vector kernels'
-// cost of moving a tile through LDS alone exceeds the whole dense product; so DD_ALGO_AUTO has no density threshold.
+// Does the shape allow the matrix-core kernels?  Then every request but DD_ALGO_VECTOR may run them.  The dense
+// contraction costs the same whatever K is and the general vector kernels cost in proportion to K, but measured over
+// K = 1 ... D/8 (`bench.py --k-sweep`) the matrix cores are ahead of those at every density, so between the two there
+// is no density threshold; the kernels for a handful of diagonals (wants_lowk) are asked first.
 bool wants_matrix(const dd_layer *l, const Shape &s)
 {
     if (l->algo == DD_ALGO_VECTOR) return false;
     // (a call without tokens launches nothing, whatever the family)
     if (!dd::product_matrix_supported(l->tokens > 0 ? l->tokens : 1, s.D, s.L, l->dtype == DD_BF16)) return false;
     return true;
+}
+
+// A handful of diagonals given as offsets and values: the kernels that visit only the stored weights and are bound by
+// reading the input and writing the output once.  DD_ALGO_VECTOR takes them wherever they apply (up to 16 diagonals);
+// DD_ALGO_AUTO where they are ahead of the dense contraction.  Their time grows with K times the width of the side the
+// lanes own, the dense contraction's with D * L, and the measured crossings (`bench.py --k-sweep`: 768^2, 1024^2,
+// 768 <-> 3072) sit at K * width = D * L / 96 for the products and at K = D / 192 for the weight gradient.
+bool wants_lowk(const dd_layer *l, const Shape &s, bool masked)
+{
+    if (l->algo != DD_ALGO_VECTOR && l->algo != DD_ALGO_AUTO) return false;
+    if (l->algo == DD_ALGO_AUTO && int64_t(l->K) * (masked ? s.D : s.L) * 96 > int64_t(s.D) * s.L) return false;
+    return dd::product_lowk_supported(l->tokens, s.D, s.L, l->K, l->dtype == DD_BF16, masked);
+}
+bool wants_lowk_wgrad(const dd_layer *l, const Shape &s)
+{
+    if (l->algo != DD_ALGO_VECTOR && l->algo != DD_ALGO_AUTO) return false;
+    if (l->algo == DD_ALGO_AUTO && int64_t(l->K) * 192 > s.D) return false;
+    return dd::weight_grad_lowk_supported(l->tokens, s.D, s.L, l->K, l->dtype == DD_BF16);
 }
 
 // the block dd_prepare fills: the operand of the forward product, then the one of the backward-input product
@@ -75,7 +92,11 @@ bool wants_matrix_wgrad(const dd_layer *l, const Shape &s)
 // the two families cut the tokens into different numbers of chunks: the size covers whichever of them runs.
 size_t weight_grad_ws_bytes(const dd_layer *l, const Shape &s)
 {
-    const size_t vector = dd::weight_grad_vector_ws_bytes(l->tokens, s.D, s.L, l->K, l->dtype == DD_BF16);
+    size_t vector = dd::weight_grad_vector_ws_bytes(l->tokens, s.D, s.L, l->K, l->dtype == DD_BF16);
+    if (wants_lowk_wgrad(l, s)) {
+        const size_t lowk = dd::weight_grad_lowk_ws_bytes(l->tokens, s.D, s.L, l->K);
+        vector = lowk > vector ? lowk : vector;
+    }
     if (!wants_matrix_wgrad(l, s)) return vector;
     const size_t matrix = dd::weight_grad_matrix_ws_bytes(l->tokens, s.D, s.L, l->K);
     if (l->algo != DD_ALGO_AUTO) return matrix;
@@ -119,7 +140,9 @@ dd_status product(const dd_layer *l, const Shape &s, bool transposed, const void
         if (transposed) a.ws = static_cast<unsigned char *>(ws) + dd::product_matrix_ws_bytes(s.D, s.L) * size_t(sets);
         (transposed ? a.src_sets : a.dst_sets) = sets;
     }
+    const bool lowk = !prepared && wants_lowk(l, s, a.masked) && aligned16(src) && aligned16(dst);
     const hipError_t e = blocks   ? dd::launch_product_blocks(a, static_cast<hipStream_t>(stream))
+                         : lowk   ? dd::launch_product_lowk(a, static_cast<hipStream_t>(stream))
                          : matrix ? dd::launch_product_matrix(a, static_cast<hipStream_t>(stream))
                                   : dd::launch_product_vector(a, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? DD_OK : DD_ERR_HIP;
@@ -297,13 +320,15 @@ dd_status dd_bwd_weight(const dd_layer *layer, const void *X, const void *dY, co
     if (!offsets || !dValues) return DD_ERR_INVALID_ARG;
     if (layer->tokens > 0 && (!X || !dY)) return DD_ERR_INVALID_ARG;
     if (dd_status st = check_ws(ws, ws_bytes, dd_workspace_bytes(DD_OP_BWD_WEIGHT, layer, 0))) return st;
-    bool matrix = wants_matrix_wgrad(layer, s);
-    if (matrix && !(aligned16(X) && aligned16(dY))) matrix = false;  // 16-byte transfers into LDS
+    const bool aligned = aligned16(X) && aligned16(dY);  // 16-byte transfers
+    const bool lowk = layer->tokens > 0 && aligned && wants_lowk_wgrad(layer, s);
+    const bool matrix = !lowk && aligned && wants_matrix_wgrad(layer, s);
     if (layer->algo != DD_ALGO_AUTO && layer->algo != DD_ALGO_VECTOR && !matrix) return DD_ERR_UNSUPPORTED;
-    // the family that runs must fit the scratch that was checked (the two cut the tokens differently)
-    const size_t runs_in = matrix ? dd::weight_grad_matrix_ws_bytes(layer->tokens, s.D, s.L, layer->K)
-                                  : dd::weight_grad_vector_ws_bytes(layer->tokens, s.D, s.L, layer->K,
-                                                                    layer->dtype == DD_BF16);
+    // the family that runs must fit the scratch that was checked (the families cut the tokens differently)
+    const size_t runs_in = lowk     ? dd::weight_grad_lowk_ws_bytes(layer->tokens, s.D, s.L, layer->K)
+                           : matrix ? dd::weight_grad_matrix_ws_bytes(layer->tokens, s.D, s.L, layer->K)
+                                    : dd::weight_grad_vector_ws_bytes(layer->tokens, s.D, s.L, layer->K,
+                                                                      layer->dtype == DD_BF16);
     if (ws_bytes < runs_in) return DD_ERR_WORKSPACE;
     dd::WeightGradArgs a;
     a.T = layer->tokens;
@@ -317,8 +342,9 @@ dd_status dd_bwd_weight(const dd_layer *layer, const void *X, const void *dY, co
     a.offsets = offsets;
     a.dValues = dValues;
     a.ws = ws;
-    const hipError_t e = matrix ? dd::launch_weight_grad_matrix(a, static_cast<hipStream_t>(hip_stream))
-                                : dd::launch_weight_grad_vector(a, static_cast<hipStream_t>(hip_stream));
+    const hipError_t e = lowk     ? dd::launch_weight_grad_lowk(a, static_cast<hipStream_t>(hip_stream))
+                         : matrix ? dd::launch_weight_grad_matrix(a, static_cast<hipStream_t>(hip_stream))
+                                  : dd::launch_weight_grad_vector(a, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? DD_OK : DD_ERR_HIP;
 }
 

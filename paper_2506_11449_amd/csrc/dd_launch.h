@@ -60,6 +60,14 @@ struct WeightGradArgs {
 };
 
 hipError_t launch_product_vector(const ProductArgs &a, hipStream_t stream);
+// vector kernels for a handful of diagonals (K <= 16, bf16 storage, feature counts multiples of 128, long side <= 8192,
+// 16-byte aligned matrices): bound by reading the input and writing the output once
+bool product_lowk_supported(int64_t T, int D, int L, int K, bool bf16, bool masked);
+hipError_t launch_product_lowk(const ProductArgs &a, hipStream_t stream);
+// the weight gradient of the same family: partial sums per workgroup, then an ordered sum over them
+bool weight_grad_lowk_supported(int64_t T, int D, int L, int K, bool bf16);
+size_t weight_grad_lowk_ws_bytes(int64_t T, int D, int L, int K);
+hipError_t launch_weight_grad_lowk(const WeightGradArgs &a, hipStream_t stream);
 
 // matrix-core family (bf16 only, feature counts multiples of 128)
 bool product_matrix_supported(int64_t T, int D, int L, bool bf16);

@@ -207,6 +207,31 @@ def test_weight_gradient_workspace_covers_whichever_family_runs(lib):
         assert sizes[binding.DD_ALGO_PREPARED] == sizes[binding.DD_ALGO_MATRIX] > 0
 
 
+def test_few_diagonals_workspace_rules(lib):
+    """The kernels for a handful of diagonals keep one block of partial sums per workgroup: at most 512 blocks and at
+    most 16 MiB of them (64 blocks where one block alone is large).  DD_ALGO_VECTOR asks for them up to 16 diagonals,
+    DD_ALGO_AUTO up to D / 192; the size covers the general vector kernels too (matrices that are not 16-byte aligned)."""
+    def need(T, M, N, K, algo, dtype=1):
+        l = _layer(T=T, M=M, N=N, K=K, dtype=dtype, algo=algo)
+        return lib.dd_workspace_bytes(binding.DD_OP_BWD_WEIGHT, ctypes.byref(l), 0)
+    V, A, X = binding.DD_ALGO_VECTOR, binding.DD_ALGO_AUTO, binding.DD_ALGO_MATRIX
+    assert need(12608, 768, 768, 4, V) == 512 * 4 * 768 * 4
+    assert need(12608, 768, 768, 16, V) == ((16 << 20) // (16 * 768 * 4)) * 16 * 768 * 4
+    assert need(3000, 512, 4096, 16, V) == 512 * 16 * 512 * 4
+    assert need(700, 1024, 4096, 16, V) == 256 * 16 * 1024 * 4
+    assert need(700, 8192, 8192, 16, V) == 64 * 16 * 8192 * 4
+    assert need(12608, 768, 768, 4, A) == max(need(12608, 768, 768, 4, V), need(12608, 768, 768, 4, X))
+    # beyond D / 192 diagonals DD_ALGO_AUTO no longer counts on these kernels; beyond sixteen nobody does
+    for K in (5, 17):
+        plain_vector = need(12608, 768, 768, K, V) if K > 16 else None
+        assert need(12608, 768, 768, K, A) >= need(12608, 768, 768, K, X)
+        if plain_vector is not None:
+            assert plain_vector < 512 * K * 768 * 4
+    # fp32 storage and widths that are no multiple of 128 never take them
+    assert need(12608, 768, 768, 4, V, dtype=0) < 512 * 4 * 768 * 4
+    assert need(12608, 700, 700, 4, V) < 512 * 4 * 700 * 4
+
+
 def test_batched_prepare_rules(lib):
     one, blk = ctypes.c_void_p(256), ctypes.c_void_p(512)
     ok = _layer(T=0, M=768, N=3072, K=30, dtype=1)
