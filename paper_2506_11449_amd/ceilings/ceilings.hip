@@ -31,8 +31,15 @@ __global__ void copy_kernel(const u32x4 *__restrict__ a, u32x4 *__restrict__ b, 
 }
 
 // 2 x 5 accumulator tiles per wave and distinct operand registers, as in the product kernel
-__global__ __launch_bounds__(256) void mfma_kernel(const bf16x8 *__restrict__ src, float *out, int iters)
+// stamps (or null): per workgroup the shader-clock counter and the 100 MHz wall clock at start and end, which
+// together give the clock the chip sustained under this load
+__global__ __launch_bounds__(256) void mfma_kernel(const bf16x8 *__restrict__ src, float *out, int iters,
+                                                   unsigned long long *stamps)
 {
+    if (stamps && threadIdx.x == 0) {
+        stamps[blockIdx.x * 4 + 0] = clock64();
+        stamps[blockIdx.x * 4 + 1] = wall_clock64();
+    }
     bf16x8 fa[2], fb[5];
     for (int i = 0; i < 2; ++i) fa[i] = src[threadIdx.x + 256 * i];
     for (int i = 0; i < 5; ++i) fb[i] = src[threadIdx.x + 256 * (2 + i)];
@@ -52,6 +59,38 @@ __global__ __launch_bounds__(256) void mfma_kernel(const bf16x8 *__restrict__ sr
         for (int b = 0; b < 5; ++b)
             for (int i = 0; i < 16; ++i) s += acc[a][b][i];
     out[blockIdx.x * 256 + threadIdx.x] = s;
+    if (stamps && threadIdx.x == 0) {
+        stamps[blockIdx.x * 4 + 2] = clock64();
+        stamps[blockIdx.x * 4 + 3] = wall_clock64();
+    }
+}
+
+// Reads only: every workgroup walks tiles of `rows` rows of `row_bytes` bytes (a tile is contiguous in memory), either
+// front to back or slice by slice -- bytes [s * slice_bytes, (s + 1) * slice_bytes) of every row, then the next s --
+// which is how the product kernels take a block of token rows 64 contraction indices at a time.
+__global__ __launch_bounds__(512) void read_kernel(const unsigned char *__restrict__ src, int rows, int row_bytes,
+                                                   int slice_bytes, long tiles, unsigned *sink)
+{
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    const long tile_bytes = long(rows) * row_bytes;
+    for (long tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+        const unsigned char *base = src + tile * tile_bytes;
+        const int per_row = slice_bytes / 16, per_slice = rows * per_row, slices = row_bytes / slice_bytes;
+        for (int s = 0; s < slices; ++s)
+            for (int i = threadIdx.x; i < per_slice; i += 512 * 4) {
+                u32x4 v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int j = i + u * 512, r = j / per_row, c = j % per_row;
+                    v[u] = j < per_slice
+                               ? *reinterpret_cast<const u32x4 *>(base + long(r) * row_bytes + s * slice_bytes + c * 16)
+                               : u32x4{0u, 0u, 0u, 0u};
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) acc ^= v[u];
+            }
+    }
+    if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x12345678u) sink[0] = 1;  // keeps the loads alive
 }
 
 __global__ __launch_bounds__(256) void fma_kernel(float *out, int iters, float m)
@@ -169,6 +208,20 @@ int main()
             CK(hipEventElapsedTime(&ms, e0, e1));
             printf("copy, %5d workgroups: %.0f GB/s (read + write)\n", blocks, 2.0 * bytes * 5 / ms / 1e6);
         }
+        // reads only, 160-row tiles of 1536-byte rows (a token block of the ViT-Base layers), 620 MB in all
+        const int rows = 160, row_bytes = 1536;
+        const long tiles = 316 * 8;
+        for (int slice_bytes : {1536, 128, 64}) {
+            for (int rep = 0; rep < 2; ++rep) {
+                CK(hipEventRecord(e0));
+                read_kernel<<<512, 512>>>((const unsigned char *)a, rows, row_bytes, slice_bytes, tiles, (unsigned *)b);
+                CK(hipEventRecord(e1));
+                CK(hipEventSynchronize(e1));
+            }
+            CK(hipEventElapsedTime(&ms, e0, e1));
+            printf("read,  512 workgroups, %4d-byte pieces of each row at a time: %.0f GB/s\n", slice_bytes,
+                   double(tiles) * rows * row_bytes / ms / 1e6);
+        }
         CK(hipFree(a));
         CK(hipFree(b));
     }
@@ -180,6 +233,9 @@ int main()
         std::vector<unsigned short> h(n);
         unsigned short *d;
         CK(hipMalloc(&d, n * 2));
+        unsigned long long *stamps;
+        CK(hipMalloc(&stamps, size_t(cus) * 4 * sizeof(unsigned long long)));
+        std::vector<unsigned long long> hs(size_t(cus) * 4);
         for (int mode = 0; mode < 2; ++mode) {
             for (size_t i = 0; i < n; ++i) {
                 const float f = mode == 0 ? 1.0f : ((rand() % 2000) - 1000) / 1000.0f;
@@ -189,16 +245,20 @@ int main()
             }
             CK(hipMemcpy(d, h.data(), n * 2, hipMemcpyHostToDevice));
             for (int iters : {48, 480, 48000}) {
-                mfma_kernel<<<cus, 256>>>((const bf16x8 *)d, out, iters);
+                mfma_kernel<<<cus, 256>>>((const bf16x8 *)d, out, iters, nullptr);
                 CK(hipDeviceSynchronize());
                 CK(hipEventRecord(e0));
-                mfma_kernel<<<cus, 256>>>((const bf16x8 *)d, out, iters);
+                mfma_kernel<<<cus, 256>>>((const bf16x8 *)d, out, iters, stamps);
                 CK(hipEventRecord(e1));
                 CK(hipEventSynchronize(e1));
                 CK(hipEventElapsedTime(&ms, e0, e1));
+                CK(hipMemcpy(hs.data(), stamps, hs.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost));
+                double ghz = 0;
+                for (int w = 0; w < cus; ++w)
+                    ghz += double(hs[w * 4 + 2] - hs[w * 4 + 0]) / (double(hs[w * 4 + 3] - hs[w * 4 + 1]) * 10.0);
                 const double fl = double(cus) * 4 * iters * 10 * 2.0 * 32 * 32 * 16;
-                printf("mfma_f32_32x32x16_bf16, %s operands, %5d MFMAs per wave: %8.3f ms, %.0f TFLOP/s\n",
-                       mode ? "random  " : "constant", iters * 10, ms, fl / ms / 1e9);
+                printf("mfma_f32_32x32x16_bf16, %s operands, %5d MFMAs per wave: %8.3f ms, %.0f TFLOP/s, shader clock %.2f GHz\n",
+                       mode ? "random  " : "constant", iters * 10, ms, fl / ms / 1e9, ghz / cus);
             }
         }
     }
