@@ -64,6 +64,9 @@ def parse():
                          "compares with and write them to bench_dense_gemm_tuned.csv (minutes)")
     ap.add_argument("--table", action="store_true", help="print the per-layer table as markdown instead of JSON")
     ap.add_argument("--k-sweep", action="store_true", help="vector family, matrix family and DD_ALGO_AUTO over K on four shapes")
+    ap.add_argument("--saturation", action="store_true",
+                    help="where the products stop scaling: prepared dd_fwd (and the dense GEMM) with 3 ... 255 result tiles "
+                         "in flight, one per CU, and on random against all-zero operands at the stack's shapes")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (a known-size reference for the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -651,6 +654,51 @@ def k_sweep(torch, dd, synth):
     return rows
 
 
+def saturation(torch, dd, synth, dense):
+    """Two experiments on the prepared forward product (and torch.matmul on the same shapes):
+    occupancy -- T = 160 * blocks tokens give blocks * N/256 result tiles of 160 x 256, one per CU, so the time per call
+    is the time of one tile with that many CUs busy; data -- the stack's shapes on random and on all-zero operands
+    (zeros switch no multiplier inputs: what is left of the difference is not arithmetic power)."""
+    out = {"occupancy": [], "data": []}
+
+    def run(T, M, N, K, zero, n=30):
+        off = torch.from_numpy(synth.draw_offsets(max(M, N), K, 2506)).cuda()
+        mk = (lambda *sh: torch.zeros(*sh, device="cuda", dtype=torch.bfloat16)) if zero else \
+             (lambda *sh: torch.randn(*sh, device="cuda").to(torch.bfloat16))
+        val = mk(K, min(M, N)) * 0.02
+        sets = 4
+        X = [mk(T, M) for _ in range(sets)]
+        Y = [torch.empty(T, N, device="cuda", dtype=torch.bfloat16) for _ in range(sets)]
+        prep = dd.dd_prepare(off, val.to(torch.bfloat16), M, N)
+        W = mk(M, N)
+        t_dd = min(time_loop(torch, lambda i: dd.dd_fwd(X[i % sets], None, None, N, Y=Y[i % sets], prepared=prep), n)
+                   for _ in range(3)) * 1e3
+        t_mm = None
+        if dense is not None:
+            dense.on()
+            t_mm = min(time_loop(torch, lambda i: torch.matmul(X[i % sets], W, out=Y[i % sets]), n) for _ in range(3)) * 1e3
+            dense.off()
+        return t_dd, t_mm
+
+    for (M, N, K) in ((768, 768, 77), (2048, 768, 205)):
+        for blocks in (1, 4, 8, 16, 32, 48, 64, 85):
+            T = 160 * blocks
+            t_dd, t_mm = run(T, M, N, K, zero=False)
+            tiles = blocks * (N // 256)
+            out["occupancy"].append({"M": M, "N": N, "tokens": T, "tiles": tiles, "dd_fwd_us": t_dd, "dense_gemm_us": t_mm,
+                                     "dd_fwd_dense_equivalent_tflops": 2.0 * T * M * N / t_dd / 1e6,
+                                     "dd_fwd_tflops_per_busy_cu": 2.0 * T * M * N / t_dd / 1e6 / tiles})
+            print(json.dumps(out["occupancy"][-1]), file=sys.stderr, flush=True)
+    for (M, N, K) in ((768, 768, 77), (768, 3072, 307), (3072, 768, 307)):
+        row = {"M": M, "N": N, "tokens": 50432}
+        for zero in (False, True):
+            t_dd, t_mm = run(50432, M, N, K, zero)
+            row["zero" if zero else "random"] = {"dd_fwd_us": t_dd, "dense_gemm_us": t_mm}
+        out["data"].append(row)
+        print(json.dumps(row), file=sys.stderr, flush=True)
+    return out
+
+
 def markdown_table(lines_by_config):
     out = ["| layer | T | K | prepare | fwd | bwd_input | bwd_weight | dense fwd / dgrad / wgrad | frac of 157.3 fwd / bwd_input / bwd_weight | fwd-only speedup (prepared / self-contained) | fwd+bwd speedup |",
            "|---|---|---|---|---|---|---|---|---|---|---|"]
@@ -690,6 +738,9 @@ def main():
         return 0
     if args.k_sweep:
         print(json.dumps({"k_sweep": k_sweep(torch, dd, synth)}))
+        return 0
+    if args.saturation:
+        print(json.dumps({"saturation": saturation(torch, dd, synth, dense)}))
         return 0
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)

@@ -498,128 +498,149 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
     bf16x8 xf0[Tl::FB], xf1[Tl::FB];
 
     // Two cursors walk the k-slices of this workgroup's tiles in order, one for the weight fragments (one slice
-    // ahead of the multiplication) and one for the token slices (four ahead).  They hold uniform values only and
-    // move without divisions or branches.  After the last slice of the last tile a cursor walks that tile again:
-    // the requests past the end only have to name valid addresses, what they fetch is never multiplied.
+    // ahead of the multiplication) and one for the token slices (four ahead).  Inside a tile a cursor only counts and
+    // the request addresses move on by a constant; the tile's place, its token block and its column tile are worked out
+    // once per tile, behind a branch every wave takes together.  After the last slice of the last tile a cursor walks
+    // that tile again: the requests past the end only have to name valid addresses, what they fetch is never
+    // multiplied.
     struct Cursor {
         int tiles_left;  // my tiles after this one
         int kt;          // k-slice inside the tile
         int tm, tn;      // the tile's place in the grouped order: row and column of the matrix described above
-        int set;         // matrix of the stack A that holds this slice
-        int set_col;     // first contraction index of the slice inside that matrix
-        int rm, rn;      // the tile itself: token block and column tile
+        int in;          // first contraction index of the slice inside its matrix of the stack A
     };
     const int hop_m = kSlots / group_n, hop_n = kSlots % group_n;  // from one of my tiles to the next
 #define DD_REAL_M(v_) (int(v_) - int(__umulhi(unsigned(v_), tiles_m_magic)) * tiles_m)
 #define DD_REAL_N(v_, c_) (int(__umulhi(unsigned(v_), tiles_m_magic)) * group_n + (c_))
-    Cursor wc = {n_mine - 1, 0, first / group_n, first % group_n, 0, 0, 0, 0};
-    wc.rm = DD_REAL_M(wc.tm);
-    wc.rn = DD_REAL_N(wc.tm, wc.tn);
+    Cursor wc = {n_mine - 1, 0, first / group_n, first % group_n, 0};
     Cursor xc = wc;
     int out_tm = wc.tm, out_tn = wc.tn;  // the tile being multiplied (place in the grouped order)
-#define DD_ADVANCE(c_) /* selects only: a branch here would split the loop body */                      \
+    // a cursor that has walked its tile's last slice: on to my next tile, if there is one
+#define DD_NEXT_TILE(c_)                                                                                \
     {                                                                                                   \
-        const int wrap = c_.kt + 1 == KT ? 1 : 0;                                                       \
-        const int move = wrap & (c_.tiles_left > 0 ? 1 : 0);                                            \
-        const int carry = c_.tn + hop_n >= group_n ? 1 : 0;                                             \
-        const int next_set = c_.set_col + kBK == a_cols ? 1 : 0;                                        \
-        const int tn1 = c_.tn + hop_n - carry * group_n, tm1 = c_.tm + hop_m + carry;                   \
-        c_.tn = move ? tn1 : c_.tn;                                                                     \
-        c_.tm = move ? tm1 : c_.tm;                                                                     \
-        c_.rm = DD_REAL_M(c_.tm);                                                                       \
-        c_.rn = DD_REAL_N(c_.tm, c_.tn);                                                                \
-        c_.tiles_left -= move;                                                                          \
-        c_.set = (c_.set + next_set) * (1 - wrap);                                                      \
-        c_.set_col = (c_.set_col + kBK) * (1 - (wrap | next_set));                                      \
-        c_.kt = (c_.kt + 1) * (1 - wrap);                                                               \
+        c_.kt = 0;                                                                                      \
+        c_.in = 0;                                                                                      \
+        if (c_.tiles_left > 0) {                                                                        \
+            --c_.tiles_left;                                                                            \
+            const int carry = c_.tn + hop_n >= group_n ? 1 : 0;                                         \
+            c_.tn += hop_n - carry * group_n;                                                           \
+            c_.tm += hop_m + carry;                                                                     \
+        }                                                                                               \
     }
-    // The token slice under xc, piece n of this thread (rows past the end re-read the last token), and the weight
-    // fragments under wc, k-step 0 of the slice, fragment row a_ of this wave: a uniform part that the scalar unit
-    // works out, plus one 32 x 32 -> 64 bit multiply-add (tokens) or a per-lane constant (weights).
     size_t w_lane[Tl::FA];
 #pragma unroll
     for (int a = 0; a < Tl::FA; ++a) w_lane[a] = (size_t(wave * (Tl::WN / 32) + a) * (KD / 16) * 64 + lane) * 8;
     const size_t w_tile_step = size_t(BN / 32) * (KD / 16) * 512;  // from one column tile to the next
     const size_t a_matrix = size_t(T) * a_cols;                    // from one matrix of the stack to the next
-#define DD_X_AT(n_)                                                                                     \
-    (A + (size_t(xc.set) * a_matrix + xc.set_col + x_col[n_]) +                                         \
-     size_t(unsigned(min(xc.rm * BM + x_row[n_], T - 1))) * unsigned(a_cols))
-#define DD_W_AT(a_) (Wf + (size_t(wc.rn) * w_tile_step + size_t(wc.kt) * 4 * 512) + w_lane[a_])
     const uint16_t *x_ptr[Tl::X_CHUNKS];  // where the next token slice to request starts, piece by piece
     const uint16_t *w_ptr[Tl::FA];        // where the next weight fragments to request start
+    // first slice of the tile under the cursor: piece n_ of this thread (rows past the end re-read the last token),
+    // fragment row a_ of this wave
+#define DD_X_TILE(n_)                                                                                   \
+    (A + x_col[n_] + size_t(unsigned(min(DD_REAL_M(xc.tm) * BM + x_row[n_], T - 1))) * unsigned(a_cols))
+#define DD_W_TILE(a_) (Wf + size_t(DD_REAL_N(wc.tm, wc.tn)) * w_tile_step + w_lane[a_])
+    // the token cursor and its addresses move on by one slice: 64 columns further on, or into the next matrix of the
+    // stack, or to the next tile
+#define DD_X_ADVANCE                                                                                    \
+    {                                                                                                   \
+        ++xc.kt;                                                                                        \
+        xc.in += kBK;                                                                                   \
+        size_t step = kBK;                                                                              \
+        if (xc.in == a_cols) {                                                                          \
+            xc.in = 0;                                                                                  \
+            step += a_matrix - size_t(a_cols);                                                          \
+        }                                                                                               \
+        if (__builtin_expect(xc.kt == KT, 0)) {                                                         \
+            DD_NEXT_TILE(xc)                                                                            \
+            _Pragma("unroll") for (int n = 0; n < Tl::X_CHUNKS; ++n) x_ptr[n] = DD_X_TILE(n);           \
+        } else {                                                                                        \
+            _Pragma("unroll") for (int n = 0; n < Tl::X_CHUNKS; ++n) x_ptr[n] += step;                  \
+        }                                                                                               \
+    }
+#define DD_W_ADVANCE                                                                                    \
+    {                                                                                                   \
+        ++wc.kt;                                                                                        \
+        if (__builtin_expect(wc.kt == KT, 0)) {                                                         \
+            DD_NEXT_TILE(wc)                                                                            \
+            _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a) w_ptr[a] = DD_W_TILE(a);                 \
+        } else {                                                                                        \
+            _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a) w_ptr[a] += 4 * 512;                     \
+        }                                                                                               \
+    }
 #define DD_LOAD_X(xg_) /* the slice under the cursor; the cursor moves on */                           \
     {                                                                                                   \
         _Pragma("unroll") for (int n = 0; n < Tl::X_CHUNKS; ++n)                                        \
-            xg_[n] = *reinterpret_cast<const u32x4 *>(DD_X_AT(n));                                      \
-        DD_ADVANCE(xc)                                                                                  \
+            xg_[n] = *reinterpret_cast<const u32x4 *>(x_ptr[n]);                                        \
+        DD_X_ADVANCE                                                                                    \
     }
-#define DD_STORE_X(xg_, g_)                                                                             \
+#define DD_STORE_X(xg_, slot_)                                                                          \
     {                                                                                                   \
-        unsigned char *dstb = smem + ((g_) % kRing) * Tl::X_BYTES;                                      \
+        unsigned char *dstb = smem + (slot_) * Tl::X_BYTES;                                             \
         _Pragma("unroll") for (int n = 0; n < Tl::X_CHUNKS; ++n)                                        \
             *reinterpret_cast<u32x4 *>(dstb + x_dst[n]) = xg_[n];                                       \
     }
 #define DD_LOAD_W(wf_)                                                                                  \
     {                                                                                                   \
-        _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a) {                                            \
-            const uint16_t *w = DD_W_AT(a);                                                             \
+        _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a)                                              \
             _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                            \
-                wf_[ks][a] = *reinterpret_cast<const bf16x8 *>(w + ks * 512);                           \
-        }                                                                                               \
-        DD_ADVANCE(wc)                                                                                  \
+                wf_[ks][a] = *reinterpret_cast<const bf16x8 *>(w_ptr[a] + ks * 512);                    \
+        DD_W_ADVANCE                                                                                    \
     }
-#define DD_LOAD_XF(xf_, g_, ks_)                                                                        \
+    // The ring of token slices: byte offsets of the stage being multiplied, the next one and the one being filled;
+    // they change places after every slice.
+    int ring_cur = 0, ring_next = Tl::X_BYTES, ring_fill = 2 * Tl::X_BYTES;
+#define DD_RING_TURN                                                                                    \
     {                                                                                                   \
-        const unsigned char *srcb = smem + ((g_) % kRing) * Tl::X_BYTES;                                \
+        const int t = ring_cur;                                                                         \
+        ring_cur = ring_next;                                                                           \
+        ring_next = ring_fill;                                                                          \
+        ring_fill = t;                                                                                  \
+    }
+#define DD_LOAD_XF(xf_, ring_, ks_)                                                                     \
+    {                                                                                                   \
+        const unsigned char *srcb = smem + (ring_);                                                     \
         const int ch = (ks_) * 2 + half;                                                                \
         _Pragma("unroll") for (int b = 0; b < Tl::FB; ++b)                                              \
             xf_[b] = *reinterpret_cast<const bf16x8 *>(srcb + b_off[b] + ((ch ^ b_sw[b]) << 4));        \
     }
-#define DD_MFMA(wf_, ks_, xf_)                                                                          \
-    _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a)                                                  \
-        _Pragma("unroll") for (int b = 0; b < Tl::FB; ++b)                                              \
-            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf_[ks_][a], xf_[b], acc[a][b], 0, 0, 0);
-#define DD_XF_ONE(xf_, g_, ks_, b_)                                                                     \
-    xf_[b_] = *reinterpret_cast<const bf16x8 *>(smem + ((g_) % kRing) * Tl::X_BYTES + b_off[b_] +       \
-                                                 ((((ks_) * 2 + half) ^ b_sw[b_]) << 4));
+#define DD_XF_ONE(xf_, ring_, ks_, b_)                                                                  \
+    xf_[b_] = *reinterpret_cast<const bf16x8 *>(smem + (ring_) + b_off[b_] + ((((ks_) * 2 + half) ^ b_sw[b_]) << 4));
     // one k-step: after each MFMA the token fragment of the following k-step for the same token tile, and one
     // piece of the slice's other traffic
-#define DD_STEP(wf_cur_, ks_, xf_cur_, xf_nxt_, g_nxt_, ks_nxt_, extra_)                                \
+#define DD_STEP(wf_cur_, ks_, xf_cur_, xf_nxt_, ring_nxt_, ks_nxt_, extra_)                             \
     _Pragma("unroll") for (int b = 0; b < Tl::FB; ++b) {                                                \
         _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a)                                              \
             acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf_cur_[ks_][a], xf_cur_[b], acc[a][b], 0, 0, 0); \
         __builtin_amdgcn_sched_barrier(0);                                                              \
-        DD_XF_ONE(xf_nxt_, g_nxt_, ks_nxt_, b)                                                          \
+        DD_XF_ONE(xf_nxt_, ring_nxt_, ks_nxt_, b)                                                       \
         extra_                                                                                          \
         __builtin_amdgcn_sched_barrier(0);                                                              \
     }
-    // One k-slice.  Its requests (weight fragments of slice g_ + 1, token slice g_ + 4) go to addresses worked out
-    // during the slice before, and the addresses for the slice after are worked out between its MFMAs, once the
-    // requests that use the old ones are out: no address arithmetic stands between the barrier and the first MFMA.
-#define DD_SLICE_X(g_, wf_cur_, wf_next_, xg_, e0_, e1_, e2_, e3_)                                       \
+    // One k-slice.  Its requests (weight fragments of the slice after it, the token slice four on) go to addresses that
+    // were settled during the slice before; once they are out, the cursors move on (k-steps 1 and 3).
+#define DD_SLICE_X(wf_cur_, wf_next_, xg_, e0_, e1_, e2_, e3_)                                           \
     {                                                                                                   \
-        unsigned char *x_dstb = smem + (((g_) + 2) % kRing) * Tl::X_BYTES;                              \
-        DD_STEP(wf_cur_, 0, xf0, xf1, g_, 1,                                                            \
+        unsigned char *x_dstb = smem + ring_fill;                                                       \
+        DD_STEP(wf_cur_, 0, xf0, xf1, ring_cur, 1,                                                      \
                 if (b < 2) { _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a) {                       \
                     wf_next_[2 * b][a] = *reinterpret_cast<const bf16x8 *>(w_ptr[a] + (2 * b) * 512);   \
                     wf_next_[2 * b + 1][a] = *reinterpret_cast<const bf16x8 *>(w_ptr[a] + (2 * b + 1) * 512); } } \
                 e0_)                                                                                    \
-        DD_STEP(wf_cur_, 1, xf1, xf0, g_, 2,                                                            \
-                if (b == 0) DD_ADVANCE(wc)                                                              \
-                if (b == 1) { _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a) w_ptr[a] = DD_W_AT(a); } \
+        DD_STEP(wf_cur_, 1, xf1, xf0, ring_cur, 2,                                                      \
+                if (b == 0) DD_W_ADVANCE                                                                \
                 e1_)                                                                                    \
-        DD_STEP(wf_cur_, 2, xf0, xf1, g_, 3,                                                            \
+        DD_STEP(wf_cur_, 2, xf0, xf1, ring_cur, 3,                                                      \
                 if (b < Tl::X_CHUNKS) { *reinterpret_cast<u32x4 *>(x_dstb + x_dst[b]) = xg_[b];         \
                                         xg_[b] = *reinterpret_cast<const u32x4 *>(x_ptr[b]); }          \
                 e2_)                                                                                    \
-        DD_STEP(wf_cur_, 3, xf1, xf0, (g_) + 1, 0,                                                      \
-                if (b == 0) DD_ADVANCE(xc)                                                              \
-                if (b >= 1 && b - 1 < Tl::X_CHUNKS) x_ptr[b - 1] = DD_X_AT(b - 1);                      \
+        DD_STEP(wf_cur_, 3, xf1, xf0, ring_next, 0,                                                     \
+                if (b == 0) DD_X_ADVANCE                                                                \
                 e3_)                                                                                    \
+        DD_RING_TURN                                                                                    \
         __syncthreads();                                                                                \
     }
-#define DD_SLICE(g_, wf_cur_, wf_next_, xg_) DD_SLICE_X(g_, wf_cur_, wf_next_, xg_, , , , )
-    static_assert(Tl::X_CHUNKS + 1 <= Tl::FB && Tl::FB >= 2, "one extra piece of work per MFMA");
+#define DD_SLICE(wf_cur_, wf_next_, xg_) DD_SLICE_X(wf_cur_, wf_next_, xg_, , , , )
+    static_assert(Tl::X_CHUNKS <= Tl::FB && Tl::FB >= 2, "one extra piece of work per MFMA");
 
     // The result on its way out.  Accumulator i of lane l is output column 8*(i/4) + 4*(l/32) + i%4 of token l%32
     // inside its 32x32 tile: four consecutive columns per group, one 8-byte LDS store.
@@ -670,6 +691,10 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
     constexpr int kOutPieces = (BM * BN / 8 + kMmThreads - 1) / kMmThreads;
     static_assert(Tl::FB == 5 && kOutPieces == 10, "the copy-out is dealt over the free places of two slices of five MFMAs per k-step");
 
+#pragma unroll
+    for (int n = 0; n < Tl::X_CHUNKS; ++n) x_ptr[n] = DD_X_TILE(n);
+#pragma unroll
+    for (int a = 0; a < Tl::FA; ++a) w_ptr[a] = DD_W_TILE(a);
     DD_LOAD_X(xg0)
     DD_LOAD_X(xg1)
     DD_LOAD_W(wf0)
@@ -677,28 +702,22 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
     DD_STORE_X(xg1, 1)
     DD_LOAD_X(xg0)
     DD_LOAD_X(xg1)
-#pragma unroll
-    for (int a = 0; a < Tl::FA; ++a) w_ptr[a] = DD_W_AT(a);  // slice 1
-#pragma unroll
-    for (int n = 0; n < Tl::X_CHUNKS; ++n) x_ptr[n] = DD_X_AT(n);  // slice 4
     __syncthreads();
-    DD_LOAD_XF(xf0, 0, 0)
-    int g = 0;
-    for (int kt = 0; kt < KT; kt += 2, g += 2) {  // the first tile
-        DD_SLICE(g, wf0, wf1, xg0)
-        DD_SLICE(g + 1, wf1, wf0, xg1)
+    DD_LOAD_XF(xf0, ring_cur, 0)
+    for (int kt = 0; kt < KT; kt += 2) {  // the first tile
+        DD_SLICE(wf0, wf1, xg0)
+        DD_SLICE(wf1, wf0, xg1)
     }
     DD_PARK
     for (int tile = 1; tile < n_mine; ++tile) {
         // first slice: the parked result goes to LDS (token tiles 0-2, then 3-4); second slice, after the barrier
         // between the two: ten pieces per thread leave for memory
-        DD_SLICE_X(g, wf0, wf1, xg0, if (b >= 2) { DD_C_WRITE(b - 2) }, if (b == 2 || b == 3) { DD_C_WRITE(b + 1) }, , )
-        DD_SLICE_X(g + 1, wf1, wf0, xg1, if (b >= 2) { DD_C_OUT(b - 2) }, if (b >= 2) { DD_C_OUT(b + 1) },
+        DD_SLICE_X(wf0, wf1, xg0, if (b >= 2) { DD_C_WRITE(b - 2) }, if (b == 2 || b == 3) { DD_C_WRITE(b + 1) }, , )
+        DD_SLICE_X(wf1, wf0, xg1, if (b >= 2) { DD_C_OUT(b - 2) }, if (b >= 2) { DD_C_OUT(b + 1) },
                    if (b >= 3) { DD_C_OUT(b + 3) }, if (b == 4) { DD_C_OUT(8) DD_C_OUT(9) })
-        g += 2;
-        for (int kt = 2; kt < KT; kt += 2, g += 2) {
-            DD_SLICE(g, wf0, wf1, xg0)
-            DD_SLICE(g + 1, wf1, wf0, xg1)
+        for (int kt = 2; kt < KT; kt += 2) {
+            DD_SLICE(wf0, wf1, xg0)
+            DD_SLICE(wf1, wf0, xg1)
         }
         DD_PARK
     }
@@ -714,11 +733,14 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
 #undef DD_SLICE_X
 #undef DD_STEP
 #undef DD_XF_ONE
-#undef DD_ADVANCE
+#undef DD_NEXT_TILE
+#undef DD_X_ADVANCE
+#undef DD_W_ADVANCE
+#undef DD_RING_TURN
 #undef DD_REAL_M
 #undef DD_REAL_N
-#undef DD_X_AT
-#undef DD_W_AT
+#undef DD_X_TILE
+#undef DD_W_TILE
 #undef DD_LOAD_X
 #undef DD_STORE_X
 #undef DD_LOAD_W
