@@ -617,7 +617,8 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
         __builtin_amdgcn_sched_barrier(0);                                                              \
     }
     // One k-slice.  Its requests (weight fragments of the slice after it, the token slice four on) go to addresses that
-    // were settled during the slice before; once they are out, the cursors move on (k-steps 1 and 3).
+    // were settled at the end of the slice before; the cursors move on behind the last MFMA, so that the branch of a
+    // tile change does not cut through the k-steps, whose instructions are dealt out by hand.
 #define DD_SLICE_X(wf_cur_, wf_next_, xg_, e0_, e1_, e2_, e3_)                                           \
     {                                                                                                   \
         unsigned char *x_dstb = smem + ring_fill;                                                       \
@@ -626,16 +627,15 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
                     wf_next_[2 * b][a] = *reinterpret_cast<const bf16x8 *>(w_ptr[a] + (2 * b) * 512);   \
                     wf_next_[2 * b + 1][a] = *reinterpret_cast<const bf16x8 *>(w_ptr[a] + (2 * b + 1) * 512); } } \
                 e0_)                                                                                    \
-        DD_STEP(wf_cur_, 1, xf1, xf0, ring_cur, 2,                                                      \
-                if (b == 0) DD_W_ADVANCE                                                                \
-                e1_)                                                                                    \
+        DD_STEP(wf_cur_, 1, xf1, xf0, ring_cur, 2, e1_)                                                 \
         DD_STEP(wf_cur_, 2, xf0, xf1, ring_cur, 3,                                                      \
                 if (b < Tl::X_CHUNKS) { *reinterpret_cast<u32x4 *>(x_dstb + x_dst[b]) = xg_[b];         \
                                         xg_[b] = *reinterpret_cast<const u32x4 *>(x_ptr[b]); }          \
                 e2_)                                                                                    \
-        DD_STEP(wf_cur_, 3, xf1, xf0, ring_next, 0,                                                     \
-                if (b == 0) DD_X_ADVANCE                                                                \
-                e3_)                                                                                    \
+        DD_STEP(wf_cur_, 3, xf1, xf0, ring_next, 0, e3_)                                                \
+        asm volatile("" ::: "memory"); /* no request sinks out of the k-steps into the branches below */ \
+        DD_W_ADVANCE                                                                                    \
+        DD_X_ADVANCE                                                                                    \
         DD_RING_TURN                                                                                    \
         __syncthreads();                                                                                \
     }
