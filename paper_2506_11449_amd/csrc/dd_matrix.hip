@@ -335,9 +335,12 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
             _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a)                                          \
                 wf_[ks][a] = *reinterpret_cast<const bf16x8 *>(w_src[a] + kk + ks * 512);               \
     }
-#define DD_LOAD_XF(xf_, kt_, ks_)                                                                       \
+    // The ring of token slices: byte offsets of the stage being multiplied, the next one and the one being filled;
+    // they change places after every slice.
+    int ring_cur = 0, ring_next = Tl::X_BYTES, ring_fill = 2 * Tl::X_BYTES;
+#define DD_LOAD_XF(xf_, ring_, ks_)                                                                     \
     {                                                                                                   \
-        const unsigned char *srcb = smem + ((kt_) % kRing) * Tl::X_BYTES;                               \
+        const unsigned char *srcb = smem + (ring_);                                                     \
         const int ch = (ks_) * 2 + half;                                                                \
         _Pragma("unroll") for (int b = 0; b < Tl::FB; ++b)                                              \
             xf_[b] = *reinterpret_cast<const bf16x8 *>(srcb + b_off[b] + ((ch ^ b_sw[b]) << 4));        \
@@ -350,15 +353,14 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
     // the current one is multiplied; then the slice two ahead is parked in LDS and a new one requested.
     // one k-step: after each MFMA the token fragment of the following k-step for the same token tile, and one
     // piece of the slice's other traffic (weight fragments of the next slice, token pieces into LDS, new requests)
-#define DD_XF_ONE(xf_, kt_, ks_, b_)                                                                    \
-    xf_[b_] = *reinterpret_cast<const bf16x8 *>(smem + ((kt_) % kRing) * Tl::X_BYTES + b_off[b_] +      \
-                                                 ((((ks_) * 2 + half) ^ b_sw[b_]) << 4));
-#define DD_STEP(wf_cur_, ks_, xf_cur_, xf_nxt_, kt_nxt_, ks_nxt_, extra_)                               \
+#define DD_XF_ONE(xf_, ring_, ks_, b_)                                                                  \
+    xf_[b_] = *reinterpret_cast<const bf16x8 *>(smem + (ring_) + b_off[b_] + ((((ks_) * 2 + half) ^ b_sw[b_]) << 4));
+#define DD_STEP(wf_cur_, ks_, xf_cur_, xf_nxt_, ring_nxt_, ks_nxt_, extra_)                               \
     _Pragma("unroll") for (int b = 0; b < Tl::FB; ++b) {                                                \
         _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a)                                              \
             acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf_cur_[ks_][a], xf_cur_[b], acc[a][b], 0, 0, 0); \
         __builtin_amdgcn_sched_barrier(0);                                                              \
-        DD_XF_ONE(xf_nxt_, kt_nxt_, ks_nxt_, b)                                                         \
+        DD_XF_ONE(xf_nxt_, ring_nxt_, ks_nxt_, b)                                                       \
         extra_                                                                                          \
         __builtin_amdgcn_sched_barrier(0);                                                              \
     }
@@ -368,16 +370,22 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
         const size_t w_kk = size_t(((kt_) + 1) < gmax ? ((kt_) + 1) : gmax) * 4 * 512;                  \
         const size_t x_kk = x_off; /* slice kt_ + 4 */                                                 \
         DD_X_ADVANCE                                                                                    \
-        unsigned char *x_dstb = smem + (((kt_) + 2) % kRing) * Tl::X_BYTES;                             \
-        DD_STEP(wf_cur_, 0, xf0, xf1, kt_, 1,                                                           \
+        unsigned char *x_dstb = smem + ring_fill;                                                       \
+        DD_STEP(wf_cur_, 0, xf0, xf1, ring_cur, 1,                                                      \
                 if (b < 2) { _Pragma("unroll") for (int a = 0; a < Tl::FA; ++a) {                       \
                     wf_next_[2 * b][a] = *reinterpret_cast<const bf16x8 *>(w_src[a] + w_kk + (2 * b) * 512); \
                     wf_next_[2 * b + 1][a] = *reinterpret_cast<const bf16x8 *>(w_src[a] + w_kk + (2 * b + 1) * 512); } }) \
-        DD_STEP(wf_cur_, 1, xf1, xf0, kt_, 2, )                                                         \
-        DD_STEP(wf_cur_, 2, xf0, xf1, kt_, 3,                                                           \
+        DD_STEP(wf_cur_, 1, xf1, xf0, ring_cur, 2, )                                                    \
+        DD_STEP(wf_cur_, 2, xf0, xf1, ring_cur, 3,                                                      \
                 if (b < Tl::X_CHUNKS) { *reinterpret_cast<u32x4 *>(x_dstb + x_dst[b]) = xg_[b];         \
                                         xg_[b] = *reinterpret_cast<const u32x4 *>(x_src[b] + x_kk); })  \
-        DD_STEP(wf_cur_, 3, xf1, xf0, (kt_) + 1, 0, )                                                   \
+        DD_STEP(wf_cur_, 3, xf1, xf0, ring_next, 0, )                                                   \
+        {                                                                                               \
+            const int t = ring_cur;                                                                     \
+            ring_cur = ring_next;                                                                       \
+            ring_next = ring_fill;                                                                      \
+            ring_fill = t;                                                                              \
+        }                                                                                               \
         __syncthreads();                                                                                \
     }
     static_assert(Tl::X_CHUNKS <= Tl::FB && Tl::FB >= 2, "one extra piece of work per MFMA");
@@ -391,7 +399,7 @@ __global__ __launch_bounds__(64 * NW) void mm_kernel(int T, int NC, int KD, int 
     DD_LOAD_X(xg0)
     DD_LOAD_X(xg1)
     __syncthreads();
-    DD_LOAD_XF(xf0, 0, 0)
+    DD_LOAD_XF(xf0, ring_cur, 0)
     for (int kt = 0; kt < KT; kt += 2) {
         DD_SLICE(kt, wf0, wf1, xg0)
         DD_SLICE(kt + 1, wf1, wf0, xg1)
