@@ -697,7 +697,9 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
                                     reinterpret_cast<u32x4 *>(parked_dst + size_t(unsigned(r)) * unsigned(c_cols))); \
     }
     constexpr int kOutPieces = (BM * BN / 8 + kMmThreads - 1) / kMmThreads;
-    static_assert(Tl::FB == 5 && kOutPieces == 10, "the copy-out is dealt over the free places of two slices of five MFMAs per k-step");
+    static_assert(Tl::FB == 5 && kOutPieces % 10 == 0, "the copy-out is dealt over ten free places of a slice of five token tiles per k-step");
+    constexpr int kPiecesPerPlace = kOutPieces / 10;
+#define DD_C_OUT_PLACE(s_) _Pragma("unroll") for (int u = 0; u < kPiecesPerPlace; ++u) { DD_C_OUT((s_) * kPiecesPerPlace + u) }
 
 #pragma unroll
     for (int n = 0; n < Tl::X_CHUNKS; ++n) x_ptr[n] = DD_X_TILE(n);
@@ -719,10 +721,10 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
     DD_PARK
     for (int tile = 1; tile < n_mine; ++tile) {
         // first slice: the parked result goes to LDS (token tiles 0-2, then 3-4); second slice, after the barrier
-        // between the two: ten pieces per thread leave for memory
+        // between the two: the pieces leave for memory
         DD_SLICE_X(wf0, wf1, xg0, if (b >= 2) { DD_C_WRITE(b - 2) }, if (b == 2 || b == 3) { DD_C_WRITE(b + 1) }, , )
-        DD_SLICE_X(wf1, wf0, xg1, if (b >= 2) { DD_C_OUT(b - 2) }, if (b >= 2) { DD_C_OUT(b + 1) },
-                   if (b >= 3) { DD_C_OUT(b + 3) }, if (b == 4) { DD_C_OUT(8) DD_C_OUT(9) })
+        DD_SLICE_X(wf1, wf0, xg1, if (b >= 2) { DD_C_OUT_PLACE(b - 2) }, if (b >= 2) { DD_C_OUT_PLACE(b + 1) },
+                   if (b >= 3) { DD_C_OUT_PLACE(b + 3) }, if (b == 4) { DD_C_OUT_PLACE(8) DD_C_OUT_PLACE(9) })
         for (int kt = 2; kt < KT; kt += 2) {
             DD_SLICE(wf0, wf1, xg0)
             DD_SLICE(wf1, wf0, xg1)
@@ -738,6 +740,7 @@ __global__ __launch_bounds__(64 * NW) void mm_persistent_kernel(int T, int NC, i
 #undef DD_PARK
 #undef DD_C_WRITE
 #undef DD_C_OUT
+#undef DD_C_OUT_PLACE
 #undef DD_SLICE_X
 #undef DD_STEP
 #undef DD_XF_ONE
