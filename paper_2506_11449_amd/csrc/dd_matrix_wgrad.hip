@@ -147,6 +147,16 @@ __global__ __launch_bounds__(kWgT, kWgPerCu) void wgrad_mm_kernel(int T, int D, 
     }
 #define DD_WG_ISSUE(s_, stage_)                                                                          \
     _Pragma("unroll") for (int i = 0; i < Tl::Rounds; ++i) DD_WG_ISSUE_PIECE(i, s_, stage_)
+    // The k-steps that lie wholly inside the chunk -- all but the last few -- need neither the row test nor the
+    // multiplication: every piece comes 16 rows after the piece of the k-step before (run[] is where the next one starts).
+    const uint16_t *run[Tl::Rounds];
+#pragma unroll
+    for (int i = 0; i < Tl::Rounds; ++i) run[i] = src_col[i] + size_t(src_row[i] + kAhead * kTS) * size_t(src_ld[i]);
+#define DD_WG_ISSUE_PIECE_INSIDE(i_, s_, stage_)                                                         \
+    {                                                                                                   \
+        global_to_lds_16(run[i_], lds_stage0 + (stage_) * kStageBytes + (i_) * (kWgT * 16));            \
+        run[i_] += size_t(kTS) * size_t(src_ld[i_]);                                                    \
+    }
     // all but the newest `n_` of this wave's transfers have landed; then the same for the whole workgroup
 #define DD_WG_ARRIVE(n_) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(n_) : "memory")
 #define DD_WG_LDS_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
@@ -207,7 +217,7 @@ __global__ __launch_bounds__(kWgT, kWgPerCu) void wgrad_mm_kernel(int T, int D, 
     // k-step j_: wait until j_+1 has landed for every wave (every wave is then also done with j_-1, whose
     // stage is requested for j_+kAhead), and multiply the fragments of j_.  The fragment reads of j_+1 and
     // the new requests are dealt out one after each MFMA, so that they issue while the matrix pipe is busy.
-#define DD_WG_STEP(j_, cur_a_, cur_b_, nxt_a_, nxt_b_)                                                   \
+#define DD_WG_STEP(j_, cur_a_, cur_b_, nxt_a_, nxt_b_, PIECE_)                                           \
     {                                                                                                   \
         DD_WG_ARRIVE((kAhead - 2) * Tl::Rounds);                                                        \
         const int next_stage = stage == kWgRing - 1 ? 0 : stage + 1;                                    \
@@ -229,7 +239,7 @@ __global__ __launch_bounds__(kWgT, kWgPerCu) void wgrad_mm_kernel(int T, int D, 
                         nxt_b_[f] = read_transposed(p, p + 4 * kBRow);                                  \
                     }                                                                                   \
                 } else {                                                                                \
-                    DD_WG_ISSUE_PIECE(k - Tl::NF, (j_) + kAhead, ahead)                                 \
+                    PIECE_(k - Tl::NF, (j_) + kAhead, ahead)                                            \
                 }                                                                                       \
             }                                                                                           \
             __builtin_amdgcn_sched_barrier(0);                                                          \
@@ -245,11 +255,17 @@ __global__ __launch_bounds__(kWgT, kWgPerCu) void wgrad_mm_kernel(int T, int D, 
     DD_WG_FRAGS(fa0, fb0, smem)
     int stage = 0;
     int j = 0;
-    for (; j < n_steps - 2; j += 2) {
-        DD_WG_STEP(j, fa0, fb0, fa1, fb1)
-        DD_WG_STEP(j + 1, fa1, fb1, fa0, fb0)
+    // k-steps whose requests (kAhead further on) lie wholly inside the chunk, two at a time
+    const int inside = min((t_end - t_begin) / kTS - kAhead, n_steps - 2);
+    for (; j + 2 <= inside; j += 2) {
+        DD_WG_STEP(j, fa0, fb0, fa1, fb1, DD_WG_ISSUE_PIECE_INSIDE)
+        DD_WG_STEP(j + 1, fa1, fb1, fa0, fb0, DD_WG_ISSUE_PIECE_INSIDE)
     }
-    DD_WG_STEP(j, fa0, fb0, fa1, fb1)
+    for (; j < n_steps - 2; j += 2) {
+        DD_WG_STEP(j, fa0, fb0, fa1, fb1, DD_WG_ISSUE_PIECE)
+        DD_WG_STEP(j + 1, fa1, fb1, fa0, fb0, DD_WG_ISSUE_PIECE)
+    }
+    DD_WG_STEP(j, fa0, fb0, fa1, fb1, DD_WG_ISSUE_PIECE)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the requests past the end have to land before the stages are reused
     DD_WG_MFMA(fa1, fb1)
 #undef DD_WG_STEP
@@ -269,6 +285,7 @@ __global__ __launch_bounds__(kWgT, kWgPerCu) void wgrad_mm_kernel(int T, int D, 
 #undef DD_WG_ENTER
     DD_WG_LDS_BARRIER();  // the table is complete and every wave is done with the stages: they become tile buffers
 #undef DD_WG_ISSUE
+#undef DD_WG_ISSUE_PIECE_INSIDE
 #undef DD_WG_ARRIVE
 #undef DD_WG_FRAGS
 #undef DD_WG_MFMA
