@@ -30,6 +30,14 @@ __global__ void copy_kernel(const u32x4 *__restrict__ a, u32x4 *__restrict__ b, 
     for (; i < n; i += stride) b[i] = a[i];
 }
 
+__global__ void fill_kernel(u32x4 *__restrict__ b, size_t n, unsigned word)
+{
+    size_t i = blockIdx.x * size_t(blockDim.x) + threadIdx.x;
+    const size_t stride = size_t(gridDim.x) * blockDim.x;
+    const u32x4 v = {word, word, word, word};
+    for (; i < n; i += stride) b[i] = v;
+}
+
 // 2 x 5 accumulator tiles per wave and distinct operand registers, as in the product kernel
 // stamps (or null): per workgroup the shader-clock counter and the 100 MHz wall clock at start and end, which
 // together give the clock the chip sustained under this load
@@ -207,6 +215,18 @@ int main()
             CK(hipEventSynchronize(e1));
             CK(hipEventElapsedTime(&ms, e0, e1));
             printf("copy, %5d workgroups: %.0f GB/s (read + write)\n", blocks, 2.0 * bytes * 5 / ms / 1e6);
+        }
+        // writes only: 2 GiB per pass, and one pass over 113 MB (the dense operands of one shape of the ViT-Base stack)
+        for (size_t fill_bytes : {bytes, size_t(113) << 20}) {
+            fill_kernel<<<8192, 256>>>(b, fill_bytes / 16, 1u);
+            CK(hipDeviceSynchronize());
+            CK(hipEventRecord(e0));
+            for (int i = 0; i < 5; ++i) fill_kernel<<<8192, 256>>>(b, fill_bytes / 16, unsigned(i));
+            CK(hipEventRecord(e1));
+            CK(hipEventSynchronize(e1));
+            CK(hipEventElapsedTime(&ms, e0, e1));
+            printf("write, 8192 workgroups, %4zu MiB per pass: %.0f GB/s, %.1f us per pass\n", fill_bytes >> 20,
+                   double(fill_bytes) * 5 / ms / 1e6, ms * 1e3 / 5);
         }
         // reads only, 160-row tiles of 1536-byte rows (a token block of the ViT-Base layers), 620 MB in all
         const int rows = 160, row_bytes = 1536;

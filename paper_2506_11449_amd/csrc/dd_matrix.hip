@@ -52,26 +52,47 @@ __device__ __forceinline__ size_t fragment_index(int j, int i, int KD)
     return ((size_t(j >> 5) * (KD >> 4) + (i >> 4)) * 64 + (j & 31) + 32 * ((i >> 3) & 1)) * 8 + (i & 7);
 }
 
+// Eight floats rounded to bf16 (nearest even, the hardware's conversion) as one 16-byte piece.
+__device__ __forceinline__ u32x4 pack_bf16x8(f32x4 lo, f32x4 hi)
+{
+    union {
+        bf16x4 h[2];
+        u32x4 w;
+    } u;
+    u.h[0] = __builtin_convertvector(lo, bf16x4);
+    u.h[1] = __builtin_convertvector(hi, bf16x4);
+    return u.w;
+}
+
 struct OperandPlace {
     int kd_total, col_step, k_step;
     size_t block_step;  // elements from one set's operand to the next where every set has an operand of its own
 };
 
 // ---------------------------------------------------------------------------------------------
-// Step 1: dense operand from the diagonals, one workgroup per output column r of the product.
+// Step 1: dense operand from the diagonals.  Operand row r belongs to output column r of the product:
 //   masked gather:  row r = q in [0, D), KD = L:  w[p] = sum_{k: (q - o_k) mod D = p < L} v_k[p]
 //   gather:         row r = p in [0, L), KD = D:  w[q] = sum_{k: (p + o_k) mod D = q} v_k[p]
-// The first `masked_rows` workgroups build rows of the masked-gather operand, the others rows of the
-// gather operand (either count may be zero).  A row is summed in fp32 in LDS (repeated offsets add, Eq. 3)
-// and rounded to bf16 once.  alpha (or null): importance weights of the D candidates (Sec. 3.2 Eq. 4); diagonal k then
-// enters as alpha[o_k] * values[k], rounded to bf16 first -- exactly the values dd_scale_values would have stored.
+// A workgroup builds kMatRows = 32 consecutive rows over kMatRange consecutive contraction indices -- one run of
+// whole fragments, contiguous in the fragment-major layout, so that it leaves in full 16-byte-per-lane stores
+// (a workgroup per row would write its 16-byte pieces 512 bytes apart, every one a partial line).
+// blockIdx.x numbers the (block of 32 rows, range of contraction indices) pairs, ranges innermost: first those of
+// the `masked_blocks` blocks of the masked-gather operand, then those of the gather operand (either count may be
+// zero).  Entries are summed in fp32 in LDS (repeated offsets add,
+// Eq. 3) and rounded to bf16 once.  alpha (or null): importance weights of the D candidates (Sec. 3.2 Eq. 4);
+// diagonal k then enters as alpha[o_k] * values[k], rounded to bf16 first -- exactly the values dd_scale_values
+// would have stored.
 // blockIdx.y numbers the sets of a group of layers of one shape whose operands are stacked into one matrix
 // (set s uses offsets + s*K and values + s*K*L): an OperandPlace says where set s goes, s*col_step columns
 // to the right (the sets' outputs side by side) or s*k_step contraction indices down (their results summed),
 // inside a matrix of kd_total contraction indices; or, for layers that merely share a launch, set s has a whole
-// operand of its own block_step elements further on.
+// operand of its own block_step elements further on.  D, L, col_step and k_step are multiples of 32.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void materialize_kernel(int D, int L, int K, int masked_rows,
+constexpr int kMatRows = 32;
+constexpr int kMatRange = 256;
+constexpr int kMatStride = kMatRange + 8;  // floats per row in LDS: the 32 rows of a fragment start 8 banks apart
+
+__global__ __launch_bounds__(256) void materialize_kernel(int D, int L, int K, int masked_blocks,
                                                           const int *__restrict__ offsets,
                                                           const uint16_t *__restrict__ values,
                                                           uint16_t *__restrict__ Wf_masked,
@@ -79,39 +100,59 @@ __global__ __launch_bounds__(256) void materialize_kernel(int D, int L, int K, i
                                                           OperandPlace place_gather,
                                                           const float *__restrict__ alpha)
 {
-    extern __shared__ float row[];
-    const bool long_major = int(blockIdx.x) < masked_rows;
-    const int r = long_major ? blockIdx.x : blockIdx.x - masked_rows;
+    __shared__ __attribute__((aligned(16))) float rows[kMatRows * kMatStride];
+    const int ranges_masked = (L + kMatRange - 1) / kMatRange, ranges_gather = (D + kMatRange - 1) / kMatRange;
+    const bool long_major = int(blockIdx.x) < masked_blocks * ranges_masked;
+    const int job = long_major ? blockIdx.x : blockIdx.x - masked_blocks * ranges_masked;
+    const int ranges = long_major ? ranges_masked : ranges_gather;
+    const int r0 = job / ranges * kMatRows;
     const int KD = long_major ? L : D;
+    const int i0 = job % ranges * kMatRange;
+    const int extent = min(kMatRange, KD - i0);
     const int set = blockIdx.y;
     offsets += size_t(set) * K;
     values += size_t(set) * K * L;
     const OperandPlace place = long_major ? place_masked : place_gather;
     uint16_t *Wf = (long_major ? Wf_masked : Wf_gather) + size_t(set) * place.block_step;
-    for (int c = threadIdx.x; c < KD; c += 256) row[c] = 0.f;
+    for (int c = threadIdx.x; c < kMatRows * kMatStride / 4; c += 256)
+        reinterpret_cast<f32x4 *>(rows)[c] = f32x4{0.f, 0.f, 0.f, 0.f};
     __syncthreads();
+    // One diagonal per thread: it meets the block where the contraction indices of the 32 rows -- consecutive
+    // modulo D from `first` on -- fall into this workgroup's range; most diagonals miss and are done after one load.
     for (int k = threadIdx.x; k < K; k += 256) {
         const int o = canonical_offset(offsets[k], D);
-        const int p = long_major ? (r - o < 0 ? r - o + D : r - o) : r;  // position along the diagonal
-        if (p >= L) continue;
-        float v = bf16_to_f32(values[size_t(k) * L + p]);
-        if (alpha) v = bf16_to_f32(f32_to_bf16(alpha[o] * v));
-        if (long_major) {
-            atomicAdd(&row[p], v);
-        } else {
-            int q = r + o;
-            if (q >= D) q -= D;
-            atomicAdd(&row[q], v);
+        int first = long_major ? r0 - o : r0 + o;  // contraction index of row r0
+        first += first < 0 ? D : 0;
+        first -= first >= D ? D : 0;
+        int d = first - i0;
+        d += d < 0 ? D : 0;
+        if (d >= extent && d + kMatRows <= D) continue;  // neither the first row inside nor a wrap into the range
+        const uint16_t *vk = values + size_t(k) * L;
+        uint16_t held[kMatRows];
+#pragma unroll
+        for (int rr = 0; rr < kMatRows; ++rr) {  // all loads first: one trip to memory, not 32
+            const int i = first + rr >= D ? first + rr - D : first + rr;
+            const int p = long_major ? i : r0 + rr;  // position along the diagonal
+            held[rr] = unsigned(i - i0) < unsigned(extent) && p < L ? vk[p] : uint16_t(0);
+        }
+        const float a = alpha ? alpha[o] : 0.f;
+#pragma unroll
+        for (int rr = 0; rr < kMatRows; ++rr) {
+            const int i = first + rr >= D ? first + rr - D : first + rr;
+            if (unsigned(i - i0) >= unsigned(extent)) continue;
+            float v = bf16_to_f32(held[rr]);
+            if (alpha) v = bf16_to_f32(f32_to_bf16(a * v));
+            atomicAdd(&rows[rr * kMatStride + i - i0], v);
         }
     }
     __syncthreads();
-    for (int c8 = threadIdx.x; c8 < KD / 8; c8 += 256) {  // 8 consecutive contraction indices = one 16-byte piece
-        u32x4 v;
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            v[e] = uint32_t(f32_to_bf16(row[c8 * 8 + 2 * e])) | (uint32_t(f32_to_bf16(row[c8 * 8 + 2 * e + 1])) << 16);
-        *reinterpret_cast<u32x4 *>(Wf + fragment_index(r + set * place.col_step, c8 * 8 + set * place.k_step,
-                                                       place.kd_total)) = v;
+    // fragments (r0 / 32, i0 / 16 ...) lie one after the other: piece `pc` is lane pc % 64 of fragment pc / 64
+    u32x4 *out = reinterpret_cast<u32x4 *>(Wf + fragment_index(r0 + set * place.col_step, i0 + set * place.k_step,
+                                                                place.kd_total));
+    for (int pc = threadIdx.x; pc < extent * 4; pc += 256) {
+        const int lane = pc & 63;
+        const float *src = rows + (lane & 31) * kMatStride + (pc >> 6) * 16 + 8 * (lane >> 5);
+        out[pc] = pack_bf16x8(*reinterpret_cast<const f32x4 *>(src), *reinterpret_cast<const f32x4 *>(src + 4));
     }
 }
 
@@ -168,11 +209,8 @@ __global__ __launch_bounds__(kSelectThreads) void select_materialize_kernel(int 
         uint16_t *Wf = long_major ? Wf_masked : Wf_gather;
         const int out_row = long_major ? r : r - D;
         for (int c8 = threadIdx.x; c8 < KD / 8; c8 += kSelectThreads) {
-            u32x4 v;
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                v[e] = uint32_t(f32_to_bf16(rows[j * D + c8 * 8 + 2 * e])) |
-                       (uint32_t(f32_to_bf16(rows[j * D + c8 * 8 + 2 * e + 1])) << 16);
+            const float *src = rows + j * D + c8 * 8;  // 4-byte aligned only: K words lie before the rows
+            const u32x4 v = pack_bf16x8(f32x4{src[0], src[1], src[2], src[3]}, f32x4{src[4], src[5], src[6], src[7]});
             *reinterpret_cast<u32x4 *>(Wf + fragment_index(out_row, c8 * 8, KD)) = v;
         }
     }
@@ -807,6 +845,13 @@ static hipError_t launch_mm(int T, int NC, int KD, int a_cols, int c_cols, const
     return hipGetLastError();
 }
 
+// workgroups of materialize_kernel: every (block of rows, range of contraction indices) pair of the two operands x sets
+static dim3 materialize_grid(int D, int L, int masked_rows, int gather_rows, int sets)
+{
+    const int ranges_masked = (L + kMatRange - 1) / kMatRange, ranges_gather = (D + kMatRange - 1) / kMatRange;
+    return dim3(masked_rows / kMatRows * ranges_masked + gather_rows / kMatRows * ranges_gather, sets);
+}
+
 hipError_t launch_prepare_matrix(int D, int L, int K, int sets, bool expanding, const int32_t *offsets,
                                  const void *values, void *forward_operand, void *backward_operand, hipStream_t stream,
                                  const float *alpha)
@@ -816,7 +861,7 @@ hipError_t launch_prepare_matrix(int D, int L, int K, int sets, bool expanding, 
     // of each other (the sets' contributions to the one input gradient add up in the contraction).
     const OperandPlace side_by_side = {expanding ? L : D, expanding ? D : L, 0, 0};
     const OperandPlace stacked = {sets * (expanding ? D : L), 0, expanding ? D : L, 0};
-    hipLaunchKernelGGL(materialize_kernel, dim3(D + L, sets), dim3(256), size_t(D) * sizeof(float), stream, D, L, K, D,
+    hipLaunchKernelGGL(materialize_kernel, materialize_grid(D, L, D, L, sets), dim3(256), 0, stream, D, L, K, D / kMatRows,
                        offsets, static_cast<const uint16_t *>(values),
                        static_cast<uint16_t *>(expanding ? forward_operand : backward_operand),
                        static_cast<uint16_t *>(expanding ? backward_operand : forward_operand),
@@ -832,7 +877,7 @@ hipError_t launch_prepare_matrix_batched(int D, int L, int K, int layers, bool e
     const size_t operand = size_t(D) * L;
     const OperandPlace masked = {L, 0, 0, 2 * operand}, gather = {D, 0, 0, 2 * operand};
     uint16_t *first = static_cast<uint16_t *>(prepared);
-    hipLaunchKernelGGL(materialize_kernel, dim3(D + L, layers), dim3(256), size_t(D) * sizeof(float), stream, D, L, K, D,
+    hipLaunchKernelGGL(materialize_kernel, materialize_grid(D, L, D, L, layers), dim3(256), 0, stream, D, L, K, D / kMatRows,
                        offsets, static_cast<const uint16_t *>(values), expanding ? first : first + operand,
                        expanding ? first + operand : first, masked, gather, static_cast<const float *>(nullptr));
     return hipGetLastError();
@@ -908,8 +953,8 @@ hipError_t launch_product_matrix(const ProductArgs &a, hipStream_t stream)
     if (!a.prepared) {
         if (a.src_sets != 1 || a.dst_sets != 1) return hipErrorInvalidValue;  // groups come prepared
         const OperandPlace place = {KD, 0, 0, 0};
-        hipLaunchKernelGGL(materialize_kernel, dim3(NC), dim3(256), size_t(KD) * sizeof(float), stream, a.D, a.L, a.K,
-                           a.masked ? NC : 0, a.offsets, static_cast<const uint16_t *>(a.values), Wf, Wf, place, place,
+        hipLaunchKernelGGL(materialize_kernel, materialize_grid(a.D, a.L, a.masked ? NC : 0, a.masked ? 0 : NC, 1), dim3(256), 0, stream, a.D, a.L, a.K,
+                           a.masked ? NC / kMatRows : 0, a.offsets, static_cast<const uint16_t *>(a.values), Wf, Wf, place, place,
                            static_cast<const float *>(nullptr));
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;

@@ -38,6 +38,14 @@ def test_two_calls_in_a_row_the_second_smaller(algo):
     _both(768, 768, 77, 4133, "bf16", a, seed=3)
 
 
+def test_a_handful_of_diagonals():
+    """K <= 16 takes kernels of its own with partial sums per token chunk: every chunk the reduction reads must have
+    been written by this call, whatever a larger call left in the array."""
+    _both(768, 768, 4, 9000, "bf16", dd.DD_ALGO_VECTOR, seed=6)
+    _both(256, 1024, 3, 333, "bf16", dd.DD_ALGO_AUTO, seed=7)
+    _both(768, 768, 16, 1200, "bf16", dd.DD_ALGO_VECTOR, seed=8)
+
+
 def test_fp32_storage_and_auto():
     _both(100, 260, 31, 1290, "f32", dd.DD_ALGO_AUTO, seed=4)
     _both(64, 64, 8, 16, "f32", dd.DD_ALGO_AUTO, seed=5)
