@@ -219,9 +219,20 @@ __global__ __launch_bounds__(kWgT, kWgPerCu) void wgrad_mm_kernel(int T, int D, 
     // the new requests are dealt out one after each MFMA, so that they issue while the matrix pipe is busy.
 #define DD_WG_STEP(j_, cur_a_, cur_b_, nxt_a_, nxt_b_, PIECE_)                                           \
     {                                                                                                   \
-        DD_WG_ARRIVE((kAhead - 2) * Tl::Rounds);                                                        \
         const int next_stage = stage == kWgRing - 1 ? 0 : stage + 1;                                    \
         const int ahead = stage == 0 ? kWgRing - 1 : stage - 1; /* (stage + kAhead) mod kWgRing */      \
+        DD_WG_STEP_BODY(j_, cur_a_, cur_b_, nxt_a_, nxt_b_, PIECE_)                                     \
+        stage = next_stage;                                                                             \
+    }
+    // a k-step in stage STAGE_, a number the compiler knows: stage addresses become instruction offsets
+#define DD_WG_STEP_FIXED(j_, cur_a_, cur_b_, nxt_a_, nxt_b_, STAGE_)                                     \
+    {                                                                                                   \
+        constexpr int next_stage = ((STAGE_) + 1) % kWgRing, ahead = ((STAGE_) + kAhead) % kWgRing;     \
+        DD_WG_STEP_BODY(j_, cur_a_, cur_b_, nxt_a_, nxt_b_, DD_WG_ISSUE_PIECE_INSIDE)                    \
+    }
+#define DD_WG_STEP_BODY(j_, cur_a_, cur_b_, nxt_a_, nxt_b_, PIECE_)                                      \
+    {                                                                                                   \
+        DD_WG_ARRIVE((kAhead - 2) * Tl::Rounds);                                                        \
         const unsigned char *base = smem + next_stage * kStageBytes;                                    \
         _Pragma("unroll") for (int m = 0; m < Tl::NM; ++m) {                                            \
             const int a = kOrder.mfma_a[m], b = kOrder.mfma_b[m];                                       \
@@ -244,9 +255,9 @@ __global__ __launch_bounds__(kWgT, kWgPerCu) void wgrad_mm_kernel(int T, int D, 
             }                                                                                           \
             __builtin_amdgcn_sched_barrier(0);                                                          \
         }                                                                                               \
-        stage = next_stage;                                                                             \
     }
     static_assert(kAhead == kWgRing - 1, "the stage requested at k-step j is the one k-step j-1 has just left");
+    static_assert(kWgRing == 6, "the loop over whole turns of the ring names its six stages");
     constexpr WgOrder<Tl::FA, Tl::FB> kOrder{};
 #pragma unroll
     for (int j = 0; j < kAhead; ++j) DD_WG_ISSUE(j, j)
@@ -257,6 +268,14 @@ __global__ __launch_bounds__(kWgT, kWgPerCu) void wgrad_mm_kernel(int T, int D, 
     int j = 0;
     // k-steps whose requests (kAhead further on) lie wholly inside the chunk, two at a time
     const int inside = min((t_end - t_begin) / kTS - kAhead, n_steps - 2);
+    for (; j + kWgRing <= inside; j += kWgRing) {  // one turn of the ring: `stage` is 0 before and after
+        DD_WG_STEP_FIXED(j, fa0, fb0, fa1, fb1, 0)
+        DD_WG_STEP_FIXED(j + 1, fa1, fb1, fa0, fb0, 1)
+        DD_WG_STEP_FIXED(j + 2, fa0, fb0, fa1, fb1, 2)
+        DD_WG_STEP_FIXED(j + 3, fa1, fb1, fa0, fb0, 3)
+        DD_WG_STEP_FIXED(j + 4, fa0, fb0, fa1, fb1, 4)
+        DD_WG_STEP_FIXED(j + 5, fa1, fb1, fa0, fb0, 5)
+    }
     for (; j + 2 <= inside; j += 2) {
         DD_WG_STEP(j, fa0, fb0, fa1, fb1, DD_WG_ISSUE_PIECE_INSIDE)
         DD_WG_STEP(j + 1, fa1, fb1, fa0, fb0, DD_WG_ISSUE_PIECE_INSIDE)
@@ -269,6 +288,8 @@ __global__ __launch_bounds__(kWgT, kWgPerCu) void wgrad_mm_kernel(int T, int D, 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the requests past the end have to land before the stages are reused
     DD_WG_MFMA(fa1, fb1)
 #undef DD_WG_STEP
+#undef DD_WG_STEP_FIXED
+#undef DD_WG_STEP_BODY
     // The table of the offsets that cross this tile: entry e stands for (column - row) = q0 - p0 - TP + 1 + e
     // (mod D) and holds the first diagonal with that offset.  (Cleared before the main loop; the barriers of
     // the loop lie between.)
