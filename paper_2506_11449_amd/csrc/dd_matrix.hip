@@ -90,6 +90,7 @@ struct OperandPlace {
 // ---------------------------------------------------------------------------------------------
 constexpr int kMatRows = 32;
 constexpr int kMatRange = 256;
+constexpr int kMatChunk = 512;             // diagonals looked at per pass
 constexpr int kMatStride = kMatRange + 8;  // floats per row in LDS: the 32 rows of a fragment start 8 banks apart
 
 __global__ __launch_bounds__(256) void materialize_kernel(int D, int L, int K, int masked_blocks,
@@ -101,6 +102,7 @@ __global__ __launch_bounds__(256) void materialize_kernel(int D, int L, int K, i
                                                           const float *__restrict__ alpha)
 {
     __shared__ __attribute__((aligned(16))) float rows[kMatRows * kMatStride];
+    __shared__ int hit_k[kMatChunk], hit_first[kMatChunk], hit_offset[kMatChunk], n_hits;
     const int ranges_masked = (L + kMatRange - 1) / kMatRange, ranges_gather = (D + kMatRange - 1) / kMatRange;
     const bool long_major = int(blockIdx.x) < masked_blocks * ranges_masked;
     const int job = long_major ? blockIdx.x : blockIdx.x - masked_blocks * ranges_masked;
@@ -116,36 +118,49 @@ __global__ __launch_bounds__(256) void materialize_kernel(int D, int L, int K, i
     uint16_t *Wf = (long_major ? Wf_masked : Wf_gather) + size_t(set) * place.block_step;
     for (int c = threadIdx.x; c < kMatRows * kMatStride / 4; c += 256)
         reinterpret_cast<f32x4 *>(rows)[c] = f32x4{0.f, 0.f, 0.f, 0.f};
-    __syncthreads();
-    // One diagonal per thread: it meets the block where the contraction indices of the 32 rows -- consecutive
-    // modulo D from `first` on -- fall into this workgroup's range; most diagonals miss and are done after one load.
-    for (int k = threadIdx.x; k < K; k += 256) {
-        const int o = canonical_offset(offsets[k], D);
-        int first = long_major ? r0 - o : r0 + o;  // contraction index of row r0
-        first += first < 0 ? D : 0;
-        first -= first >= D ? D : 0;
-        int d = first - i0;
-        d += d < 0 ? D : 0;
-        if (d >= extent && d + kMatRows <= D) continue;  // neither the first row inside nor a wrap into the range
-        const uint16_t *vk = values + size_t(k) * L;
-        uint16_t held[kMatRows];
+    // A diagonal meets the block where the contraction indices of the 32 rows -- consecutive modulo D from `first`
+    // on -- fall into this workgroup's range; most diagonals miss.  Up to kMatChunk diagonals at a time: every thread
+    // looks at its share of the offsets (all loads first: one trip to memory) and lists the ones that meet the block;
+    // then the (listed diagonal, row) pairs are dealt to all threads, rows innermost, so that a wave reads runs of
+    // 32 consecutive values.
+    for (int k0 = 0; k0 < K; k0 += kMatChunk) {
+        if (threadIdx.x == 0) n_hits = 0;
+        int o[kMatChunk / 256];
 #pragma unroll
-        for (int rr = 0; rr < kMatRows; ++rr) {  // all loads first: one trip to memory, not 32
-            const int i = first + rr >= D ? first + rr - D : first + rr;
-            const int p = long_major ? i : r0 + rr;  // position along the diagonal
-            held[rr] = unsigned(i - i0) < unsigned(extent) && p < L ? vk[p] : uint16_t(0);
+        for (int j = 0; j < kMatChunk / 256; ++j) {
+            const int k = k0 + j * 256 + threadIdx.x;
+            o[j] = k < K ? offsets[k] : 0;
         }
-        const float a = alpha ? alpha[o] : 0.f;
+        __syncthreads();
 #pragma unroll
-        for (int rr = 0; rr < kMatRows; ++rr) {
-            const int i = first + rr >= D ? first + rr - D : first + rr;
-            if (unsigned(i - i0) >= unsigned(extent)) continue;
-            float v = bf16_to_f32(held[rr]);
-            if (alpha) v = bf16_to_f32(f32_to_bf16(a * v));
+        for (int j = 0; j < kMatChunk / 256; ++j) {
+            const int k = k0 + j * 256 + threadIdx.x;
+            if (k >= K) continue;
+            const int oc = canonical_offset(o[j], D);
+            int first = long_major ? r0 - oc : r0 + oc;  // contraction index of row r0
+            first += first < 0 ? D : 0;
+            first -= first >= D ? D : 0;
+            int d = first - i0;
+            d += d < 0 ? D : 0;
+            if (d >= extent && d + kMatRows <= D) continue;  // neither the first row inside nor a wrap into the range
+            const int slot = atomicAdd(&n_hits, 1);
+            hit_k[slot] = k;
+            hit_first[slot] = first;
+            hit_offset[slot] = oc;
+        }
+        __syncthreads();
+        const int items = n_hits * kMatRows;
+        for (int item = threadIdx.x; item < items; item += 256) {
+            const int h = item / kMatRows, rr = item % kMatRows;
+            const int i = hit_first[h] + rr >= D ? hit_first[h] + rr - D : hit_first[h] + rr;
+            const int p = long_major ? i : r0 + rr;  // position along the diagonal
+            if (unsigned(i - i0) >= unsigned(extent) || p >= L) continue;
+            float v = bf16_to_f32(values[size_t(hit_k[h]) * L + p]);
+            if (alpha) v = bf16_to_f32(f32_to_bf16(alpha[hit_offset[h]] * v));
             atomicAdd(&rows[rr * kMatStride + i - i0], v);
         }
+        __syncthreads();  // the list may be overwritten; after the last pass: the rows are complete
     }
-    __syncthreads();
     // fragments (r0 / 32, i0 / 16 ...) lie one after the other: piece `pc` is lane pc % 64 of fragment pc / 64
     u32x4 *out = reinterpret_cast<u32x4 *>(Wf + fragment_index(r0 + set * place.col_step, i0 + set * place.k_step,
                                                                 place.kd_total));
