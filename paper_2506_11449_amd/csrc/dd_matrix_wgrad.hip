@@ -110,6 +110,14 @@ __global__ __launch_bounds__(kWgT, kWgPerCu) void wgrad_mm_kernel(int T, int D, 
     const int split = (local / tiles) * kWgXcds + xcd;
     if (split >= splits) return;
     const int tile = local % tiles;
+    // The two workgroups of a CU (an XCD's workgroup i and i + 32) take turns at the higher wave priority, k-step by
+    // k-step.  Left alone the one dispatched first stays ahead and the two halves of the XCD drift apart by more
+    // tokens than the L2 holds, so that what they share is fetched twice (768 <-> 3072 at 50432 tokens: 476 MB per
+    // launch; taking turns: 388 MB, each byte once, and 1 % less time).  Only for the 192 x 192 tile: the 128 x 256
+    // tile of the shapes that 192 does not divide fetches less this way too (1024 <-> 4096: 397 -> 310 MB) but
+    // runs 3 % longer.
+    constexpr bool kTakeTurns = TP == 192 && TQ == 192;
+    const bool second = (local >> 5) & 1;
     const int p0 = (tile % tiles_p) * TP, q0 = (tile / tiles_p) * TQ;
     // Chunk `split` owns the 32-token slices [begin(split), begin(split + 1)), begin(s) = s * slices / splits
     // + skew * (2 min(s, splits / 2) - s): the chunks of the first half of the workgroups are `skew` slices longer
@@ -234,6 +242,9 @@ __global__ __launch_bounds__(kWgT, kWgPerCu) void wgrad_mm_kernel(int T, int D, 
 #define DD_WG_STEP_FIXED(j_, cur_a_, cur_b_, nxt_a_, nxt_b_, STAGE_)                                     \
     {                                                                                                   \
         constexpr int next_stage = ((STAGE_) + 1) % kWgRing, ahead = ((STAGE_) + kAhead) % kWgRing;     \
+        if constexpr (kTakeTurns) {                                                                     \
+            if ((((STAGE_) & 1) != 0) == second) asm volatile("s_setprio 1"); else asm volatile("s_setprio 0"); \
+        }                                                                                               \
         DD_WG_STEP_BODY(j_, cur_a_, cur_b_, nxt_a_, nxt_b_, DD_WG_ISSUE_PIECE_INSIDE)                    \
     }
 #define DD_WG_STEP_BODY(j_, cur_a_, cur_b_, nxt_a_, nxt_b_, PIECE_)                                      \
@@ -282,6 +293,7 @@ __global__ __launch_bounds__(kWgT, kWgPerCu) void wgrad_mm_kernel(int T, int D, 
         DD_WG_STEP_FIXED(j + 4, fa0, fb0, fa1, fb1, 4)
         DD_WG_STEP_FIXED(j + 5, fa1, fb1, fa0, fb0, 5)
     }
+    if constexpr (kTakeTurns) asm volatile("s_setprio 0");
     for (; j + 2 <= inside; j += 2) {
         DD_WG_STEP(j, fa0, fb0, fa1, fb1, DD_WG_ISSUE_PIECE_INSIDE)
         DD_WG_STEP(j + 1, fa1, fb1, fa0, fb0, DD_WG_ISSUE_PIECE_INSIDE)
