@@ -25,6 +25,7 @@ import argparse
 import json
 import os
 import sys
+import tempfile
 import time
 
 import numpy as np
@@ -629,7 +630,7 @@ def tune_dense(torch, dd, synth, dense):
             f.write(f"Validator,{key},{val}\n")
         for r in dense.tunable.get_results():
             f.write(",".join(str(x) for x in r) + "\n")
-    dense.tunable.set_filename(os.path.join(ROOT, "gpurun_out", "tunableop_scratch.csv"))  # torch's own copy at exit
+    dense.tunable.set_filename(os.path.join(tempfile.gettempdir(), "tunableop_scratch.csv"))  # torch's own copy at exit
     print(f"wrote {DENSE_TUNING_FILE}", file=sys.stderr)
 
 
