@@ -485,11 +485,11 @@ def run_stack(args, torch, dd, synth, dense):
         S = g.sets
         j0 = 0
         us = {"dd_fwd": time_loop(torch, lambda i: dd.dd_fwd(g.X[i % S], None, None, g.N, Y=g.Y[i % S],
-                                                             prepared=g.prepared[j0]), 20) * 1e3,
+                                                             prepared=g.prepared[j0]), 50, warmup=10) * 1e3,
               "dd_bwd_input": time_loop(torch, lambda i: dd.dd_bwd_input(g.dY[i % S], None, None, g.M, dX=g.dX[i % S],
-                                                                         prepared=g.prepared[j0]), 20) * 1e3,
+                                                                         prepared=g.prepared[j0]), 50, warmup=10) * 1e3,
               "dd_bwd_weight": time_loop(torch, lambda i: dd.dd_bwd_weight(g.X[i % S], g.dY[i % S], g.offsets[j0],
-                                                                           dValues=g.dValues[j0], ws=st.ws), 20) * 1e3}
+                                                                           dValues=g.dValues[j0], ws=st.ws), 50, warmup=10) * 1e3}
         line = {"layers": g.n_layers, "K": g.K, "us": us,
                 "frac_of_fp32_vector_peak": {k: 2.0 * st.tokens * g.K * g.L / v / 1e6 / VALU_FP32_PEAK_TFLOPS
                                              for k, v in us.items()},
