@@ -74,7 +74,7 @@ def parse():
     return ap.parse_args()
 
 
-def time_loop(torch, fn, n, warmup=3):
+def time_loop(torch, fn, n, warmup=5):
     """Average milliseconds per call of fn(i), timed with events on the launch stream."""
     for i in range(warmup):
         fn(i)
@@ -258,6 +258,8 @@ class LayerBench:
     def measure(self, n, dense=None):
         """One sub-line: us per entry point, rates, and the comparison with the dense GEMMs."""
         torch = self.torch
+        for i in range(30):  # fresh buffers and an idle chip: the first dozen milliseconds run slow
+            self.step(i)
         us = {"dd_select_diagonals": time_loop(torch, self.select, n) * 1e3,
               "dd_fwd": time_loop(torch, self.fwd, n) * 1e3,
               "dd_bwd_input": time_loop(torch, self.bwd_input, n) * 1e3,
@@ -599,7 +601,7 @@ def config_sublines(args, torch, dd, synth, dense):
         lines = []
         for i, l in enumerate(distinct(synth.WORKLOADS[name])):
             b = LayerBench(torch, dd, synth, l, "auto", 0, 0, seed=2506 + i)
-            lines.append(b.measure(30 if l.tokens < 20000 else 15, dense))
+            lines.append(b.measure(30, dense))
             if name == "vitb_attn_proj":
                 lines[-1]["selection_helpers_us"] = helper_paths(b, 30)
             del b
