@@ -709,7 +709,8 @@ def markdown_table(lines_by_config):
         for l in lines:
             us, g, sp = l["us"], l.get("dense_gemm_us"), l.get("speedup_vs_dense")
             fr = l["frac_of_fp32_vector_peak"]
-            out.append(f"| {l['layer']} ({name}) | {l['tokens']} | {l['K']} | {us.get('dd_prepare', float('nan')):.1f} | "
+            prep = f"{us['dd_prepare']:.1f}" if "dd_prepare" in us else "-"  # fp32 storage has no dense operand
+            out.append(f"| {l['layer']} ({name}) | {l['tokens']} | {l['K']} | {prep} | "
                        f"{us['dd_fwd']:.1f} | {us['dd_bwd_input']:.1f} | {us['dd_bwd_weight']:.1f} | " +
                        (f"{g['fwd']:.1f} / {g['dgrad']:.1f} / {g['wgrad']:.1f}" if g else "") + " | " +
                        f"{fr['dd_fwd']:.2f} / {fr['dd_bwd_input']:.2f} / {fr['dd_bwd_weight']:.2f} | " +
