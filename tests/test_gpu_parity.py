@@ -494,3 +494,45 @@ def test_block_skipping_needs_offsets_and_a_prepared_block():
     assert lib.dd_fwd(ctypes.byref(l), one, one, None, one, one, need - 1, None) == 3   # block too small
     l32 = dd.make_layer(64, 768, 768, 77, torch.float32, dd.DD_ALGO_BLOCKS)
     assert lib.dd_fwd(ctypes.byref(l32), one, one, None, one, one, need, None) == 2     # fp32 storage
+
+
+@pytest.mark.parametrize("M,N,K", [(3072, 768, 307), (768, 3072, 307), (3072, 768, 4), (768, 3072, 4)])
+def test_more_than_2_31_elements(M, N, K):
+    """700001 tokens through a 3072-wide side: the wide matrix has 2.15e9 elements (4.3 GB), so the rows past token 699050
+    start beyond 2^31 elements.  Inputs are drawn on the device; the token rows checked against the oracle include the
+    first ones past that limit and the last; the weight gradient is checked through a property that holds at any size --
+    it is additive over token ranges (each half has fewer than 2^31 elements and such sizes are checked against the
+    oracle elsewhere) -- and on sampled entries against the oracle over a window of tokens with all others zeroed."""
+    T, D, L = 700001, max(M, N), min(M, N)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(M + K)
+    X = torch.randn((T, M), device="cuda", generator=gen, dtype=torch.float32).to(torch.bfloat16)
+    dY = torch.randn((T, N), device="cuda", generator=gen, dtype=torch.float32).to(torch.bfloat16)
+    offsets = synth.draw_offsets(D, K, seed=5)
+    values = synth.round_to_bf16(synth.draw_normal((K, L), 0.02, 5, 10))
+    d_off, d_val = torch.from_numpy(offsets).cuda(), to_dev(values, "bf16")
+    Y = dd.dd_fwd(X, d_off, d_val, N)
+    dX = dd.dd_bwd_input(dY, d_off, d_val, M)
+    limit = (1 << 31) // D  # first token row that starts past 2^31 elements of the wide matrix
+    rng = np.random.default_rng(1)
+    rows = np.unique(np.concatenate([[0, limit - 1, limit, limit + 1, T - 2, T - 1], rng.integers(0, T, 24),
+                                     rng.integers(limit, T, 24)]))
+    idx = torch.from_numpy(rows).cuda()
+    assert rel_err(to_host(Y[idx]), orc.fwd(to_host(X[idx]), offsets, values, N)) <= TOL["bf16"]
+    assert rel_err(to_host(dX[idx]), orc.bwd_input(to_host(dY[idx]), offsets, values, M)) <= TOL["bf16"]
+    del Y, dX
+    dV = dd.dd_bwd_weight(X, dY, d_off)
+    half = 350000
+    dV_a = dd.dd_bwd_weight(X[:half], dY[:half], d_off)
+    dV_b = dd.dd_bwd_weight(X[half:], dY[half:], d_off)
+    assert rel_err(to_host(dV), to_host(dV_a) + to_host(dV_b)) <= TOL_DV
+    # a window of 64 tokens around the limit and the last 64 kept, everything else zero: the full-size call then
+    # has to find exactly those rows, and the oracle needs only them
+    keep = np.concatenate([np.arange(limit - 32, limit + 32), np.arange(T - 64, T)])
+    kidx = torch.from_numpy(keep).cuda()
+    Xk, dYk = X[kidx].clone(), dY[kidx].clone()
+    X.zero_()
+    dY.zero_()
+    X[kidx], dY[kidx] = Xk, dYk
+    dV_w = dd.dd_bwd_weight(X, dY, d_off)
+    assert rel_err(to_host(dV_w), orc.bwd_weight(to_host(Xk), to_host(dYk), offsets)) <= TOL_DV
